@@ -1,0 +1,191 @@
+/*
+ * nat.h -- C ABI of the partial-token GRPO loss stage of NAT ("Not All Tokens
+ * are Needed") for AMD MI355X (gfx950).
+ *
+ * Path:  rewards -> nat_advantage -> nat_select -> nat_compact -> nat_loss_fwd_bwd
+ *
+ * Notation follows the paper: P prompts, G rollouts per prompt, B = P*G
+ * rollouts, T_i response length of rollout i, t = 1..T_i token position,
+ * m_{i,t} selection mask, p_{i,t} inclusion probability, L_i RPC cut point,
+ * C minimum retained prefix, A_i group-relative advantage, r_{i,t} importance
+ * ratio, S_{i,t} clipped surrogate.  Response tokens of all rollouts are
+ * packed back to back: token (i, t) sits at packed position
+ * cu_seqlens[i] + (t - 1); N = cu_seqlens[B] tokens in total, N_k kept.
+ *
+ * Conventions
+ *   - every pointer named d_* is DEVICE memory, h_* is HOST memory;
+ *   - the library never allocates or frees device memory: all buffers,
+ *     including workspaces, belong to the caller (query the *_workspace_bytes
+ *     functions);
+ *   - all work is enqueued on the caller's stream (`stream` is a hipStream_t
+ *     passed as void*; NULL = the default stream); no call synchronises with
+ *     the host;
+ *   - outputs are fully overwritten unless stated otherwise;
+ *   - every function returns a nat_status and never throws; argument errors
+ *     are detected on the host before anything is launched.
+ */
+#ifndef NAT_H_
+#define NAT_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef int32_t nat_status;
+enum {
+  NAT_OK = 0,
+  NAT_INVALID_ARG = 1,          /* NULL required pointer, parameter out of range      */
+  NAT_BAD_SHAPE = 2,            /* size not supported by the kernels                   */
+  NAT_WORKSPACE_TOO_SMALL = 3,
+  NAT_UNSUPPORTED_DTYPE = 4,
+  NAT_HIP_ERROR = 5             /* a HIP runtime call failed (launch, copy, event)     */
+};
+
+enum { NAT_SCHEME_FULL = 0, NAT_SCHEME_URS = 1, NAT_SCHEME_RPC = 2, NAT_SCHEME_DET = 3 };
+enum { NAT_DTYPE_F32 = 0, NAT_DTYPE_BF16 = 1 };
+
+/* Human-readable name of a status code (static string, never NULL). */
+const char* nat_status_string(nat_status s);
+
+/*
+ * Selection parameters (Sec. 3.1 and Sec. 4 of the paper).
+ *   scheme      FULL: every token, p_{i,t} = 1 (full-token GRPO, Eq. 5).
+ *               URS:  m_{i,t} ~ Bernoulli(p) i.i.d., p_{i,t} = p (Sec. 3.1).
+ *               RPC:  L_i ~ Uniform{C_i..T_i}, C_i = min(max(C,1),T_i),
+ *                     m_{i,t} = 1{t <= L_i} (Eq. 7), p_{i,t} = 1 for t <= C_i and
+ *                     (T_i-t+1)/(T_i-C_i+1) after (Eq. 8; Sec. 4 "Minimum-cutoff RPC").
+ *               DET:  keep the first K_i = floor(trunc_frac*T_i) tokens, weight as if
+ *                     p = 1 (the biased control of Sec. 4).
+ *   Random bits: Philox4x32-10, key = (seed low, seed high), counter =
+ *   (t0 >> 2, rollout_id_base + i, stream, step) with t0 = t - 1; stream 0 = URS
+ *   token draws (word t0 & 3 of the block; keep iff word < floor(p * 2^32)),
+ *   stream 1 = RPC cut (word 0; L_i = C_i + ((word * n) >> 32), n = T_i-C_i+1).
+ *   A draw depends only on (seed, step, global rollout id, t), so it does not
+ *   change with batching or sharding.
+ *   d_scheme_per_rollout: optional DEVICE array [B] overriding `scheme` per
+ *   rollout (mixed batches); NULL = uniform scheme.
+ */
+typedef struct nat_select_params {
+  int32_t scheme;
+  int32_t min_cut;           /* C >= 1 (RPC)                       */
+  double p;                  /* URS keep probability, in (0, 1]    */
+  double trunc_frac;         /* DET fraction beta, in (0, 1]       */
+  uint64_t seed;
+  uint32_t step;
+  int32_t rollout_id_base;   /* global id of rollout 0 of this batch */
+  const int32_t* d_scheme_per_rollout;
+} nat_select_params;
+
+/*
+ * Group-relative advantage, Eq. 2:  A = (R - mean) / (std + eps_adv) with the
+ * population standard deviation over the G rollouts of each prompt.
+ *   d_rewards [P*G] float32 (prompt-major), d_adv [P*G] float32 out.
+ * Errors: NULL pointer, P <= 0, G <= 0, eps_adv < 0 -> NAT_INVALID_ARG.
+ */
+nat_status nat_advantage(const float* d_rewards, int32_t P, int32_t G, float eps_adv,
+                         float* d_adv, void* stream);
+
+/* Number of uint32 words of the packed mask of N tokens: 2 * ceil(N / 64). */
+int64_t nat_mask_words(int64_t N);
+
+/*
+ * Draw the selection mask (Sec. 3.1 "Random masking", Eq. 7).
+ *   d_cu_seqlens [B+1] int64, non-decreasing, cu_seqlens[0] = 0, cu_seqlens[B] = N
+ *                (the host passes N so that no read-back is needed);
+ *   d_cut_len    [B] int32 out: L_i (RPC), K_i (DET), T_i (FULL, URS);
+ *   d_mask_bits  [nat_mask_words(N)] uint32 out: bit (n & 31) of word n >> 5 is the
+ *                mask of packed position n; bits at positions >= N are zero.
+ * Errors: NULL pointer, B <= 0, N < 0 or N >= 2^31, unknown scheme, p outside (0,1],
+ * min_cut < 1, trunc_frac outside (0,1] -> NAT_INVALID_ARG.  N = 0 is valid.
+ */
+nat_status nat_select(const nat_select_params* params, const int64_t* d_cu_seqlens, int32_t B,
+                      int64_t N, int32_t* d_cut_len, uint32_t* d_mask_bits, void* stream);
+
+/* Bytes of device workspace nat_compact needs for N tokens. */
+size_t nat_compact_workspace_bytes(int64_t N);
+
+/*
+ * Stable mask -> index compaction with the Horvitz-Thompson weight of every
+ * kept token (Eq. 6 / Eq. 9 folded with the 1/G * 1/|o_i| averaging of Eq. 5):
+ *     kept_w = 1 / (n_rollouts_global * T_i * p_{i,t})   (one fp64 division, rounded to fp32)
+ * with p_{i,t} recomputed from (scheme, p, C, T_i, t) of `params`.
+ *   d_kept_idx [cap] int32 out: packed positions of kept tokens, ascending;
+ *   d_kept_seq [cap] int32 out: rollout index i of each kept token;
+ *   d_kept_w   [cap] float out;      cap >= number of kept tokens (N always suffices);
+ *   d_cu_kept  [B+1] int32 out: kept-token offsets per rollout;
+ *   d_n_kept   [1] int32 out;  h_n_kept: optional PINNED host int32 that receives the
+ *              same value by an asynchronous copy on `stream` (NULL = skip);
+ *   optional gather (any of the three pairs may be NULL):
+ *     d_hidden [N, H] -> d_hidden_k [cap, H] rows of kept tokens, dtype NAT_DTYPE_*,
+ *     d_ids [N] -> d_ids_k [cap],  d_old_logp [N] -> d_old_logp_k [cap];
+ *   d_ws / ws_bytes: workspace of at least nat_compact_workspace_bytes(N).
+ * Errors: as nat_select, plus n_rollouts_global <= 0, H <= 0 or a row size that is not
+ * a multiple of 16 bytes when gathering -> NAT_BAD_SHAPE, workspace too small.
+ */
+nat_status nat_compact(const nat_select_params* params, int32_t n_rollouts_global,
+                       const uint32_t* d_mask_bits, const int64_t* d_cu_seqlens, int32_t B, int64_t N,
+                       int32_t* d_kept_idx, int32_t* d_kept_seq, float* d_kept_w, int32_t* d_cu_kept,
+                       int32_t* d_n_kept, int32_t* h_n_kept,
+                       const void* d_hidden, void* d_hidden_k, int32_t H, int32_t dtype,
+                       const int32_t* d_ids, int32_t* d_ids_k,
+                       const float* d_old_logp, float* d_old_logp_k,
+                       void* d_ws, size_t ws_bytes, void* stream);
+
+/*
+ * Workspace for nat_loss_fwd_bwd.  *_bytes is the recommended size (largest
+ * token chunk the kernels use); *_min_bytes the smallest size accepted (one
+ * token tile per chunk).  Both return 0 for unsupported arguments.
+ */
+size_t nat_loss_workspace_bytes(int32_t N_k, int32_t H, int32_t V, int32_t dtype);
+size_t nat_loss_workspace_min_bytes(int32_t N_k, int32_t H, int32_t V, int32_t dtype);
+
+/*
+ * LM-head projection, full-vocabulary log-softmax, clipped-ratio GRPO surrogate
+ * and its gradients on the kept tokens (Eq. 1, Eq. 3, Eq. 5, Eq. 6/9; App. A):
+ *     z_k = W h_k,  logp_k = z_k[ids_k] - logsumexp(z_k),
+ *     r_k = exp(logp_k - old_logp_k),  A = adv[kept_seq[k]],
+ *     S_k = min(r_k A, clip(r_k, 1-eps_lo, 1+eps_hi) A),
+ *     loss = - sum_k kept_w[k] S_k                     (the paper maximises J; loss = -J_hat)
+ *     c_k = -grad_scale * kept_w[k] * dS_k/dlogp_k,  dS/dlogp = r A if (A>0 and r<=1+eps_hi)
+ *                                                     or (A<0 and r>=1-eps_lo), else 0,
+ *     dz_k = c_k (onehot(ids_k) - softmax(z_k)),  dH_k = W^T dz_k,  dW = sum_k dz_k h_k^T.
+ * The KL term of Eq. 4 is not included (beta = 0 as in Sec. 5.1).
+ *   d_hidden_k [N_k, H] row-major, dtype bf16 or f32;  d_W [V, H] row-major, same dtype;
+ *   d_ids_k [N_k] int32 in [0, V);  d_old_logp_k [N_k] float;  d_adv [>= max(kept_seq)+1] float;
+ *   d_loss [1] float out;  d_logp_k [N_k] float out or NULL;
+ *   d_dH_k [N_k, H] out, same dtype as the inputs;
+ *   d_dW [V, H] float32 out: overwritten, or added to when accumulate_dw != 0.
+ *   The reduction order of d_dW and d_loss is fixed: results are bit-identical from run to run.
+ *   The [N_k, V] logits are never written to memory as a whole; the bf16 path keeps a
+ *   bounded bf16 tile of soft-max numerators for one token chunk in the workspace.
+ * N_k = 0 is valid: loss = 0, d_dW zeroed unless accumulating, d_dH_k untouched.
+ * Errors: NULL pointer, N_k < 0, eps < 0 -> NAT_INVALID_ARG; H <= 0, V <= 0, or (bf16) H not
+ * a multiple of 64 -> NAT_BAD_SHAPE; dtype unknown -> NAT_UNSUPPORTED_DTYPE; ws_bytes below
+ * nat_loss_workspace_min_bytes -> NAT_WORKSPACE_TOO_SMALL.
+ */
+nat_status nat_loss_fwd_bwd(const void* d_hidden_k, const void* d_W, const int32_t* d_ids_k,
+                            const float* d_old_logp_k, const float* d_adv, const int32_t* d_kept_seq,
+                            const float* d_kept_w, int32_t N_k, int32_t H, int32_t V, int32_t dtype,
+                            float eps_lo, float eps_hi, float grad_scale,
+                            float* d_loss, float* d_logp_k, void* d_dH_k, float* d_dW,
+                            int32_t accumulate_dw, void* d_ws, size_t ws_bytes, void* stream);
+
+/*
+ * Per-kernel timing (measurement aid, off by default).  When enabled, every
+ * kernel launch of the library is bracketed by a pair of HIP events on the
+ * caller's stream.  nat_profile_collect waits for those events, adds the elapsed
+ * milliseconds and launch counts per kernel class into the caller's HOST arrays
+ * (length n_classes = nat_profile_num_classes()) and clears the record.
+ */
+int32_t nat_profile_num_classes(void);
+const char* nat_profile_class_name(int32_t cls);
+nat_status nat_profile_enable(int32_t on);
+nat_status nat_profile_collect(double* h_ms, int64_t* h_launches, int32_t n_classes);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* NAT_H_ */

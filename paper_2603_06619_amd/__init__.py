@@ -1,0 +1,12 @@
+"""MI355X-native partial-token GRPO loss stage of NAT: thin Python binding over
+the C-ABI library libnat_hip.so (hand-written HIP kernels for gfx950).
+
+Every step of the path runs inside the library; this package only marshals
+arguments (torch tensors -> device pointers, the current HIP stream)."""
+from .binding import (  # noqa: F401
+    NatError, SelectParams, FULL, URS, RPC, DET, DTYPE_F32, DTYPE_BF16,
+    load_library, library_path, status_string, mask_words,
+    nat_advantage, nat_select, nat_compact, nat_loss_fwd_bwd,
+    compact_workspace_bytes, loss_workspace_bytes, loss_workspace_min_bytes,
+    profile_enable, profile_collect,
+)

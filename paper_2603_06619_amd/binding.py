@@ -1,0 +1,186 @@
+"""ctypes binding of include/nat.h.  Argument marshalling only."""
+import ctypes
+import os
+
+import torch
+
+_PKG_DIR = os.path.dirname(os.path.abspath(__file__))
+_LIB_NAME = "libnat_hip.so"
+_lib = None
+
+FULL, URS, RPC, DET = 0, 1, 2, 3
+DTYPE_F32, DTYPE_BF16 = 0, 1
+
+
+class NatError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = status
+        super().__init__(f"{where} failed: {status_string(status)} ({status})")
+
+
+class _CSelectParams(ctypes.Structure):
+    _fields_ = [("scheme", ctypes.c_int32), ("min_cut", ctypes.c_int32), ("p", ctypes.c_double),
+                ("trunc_frac", ctypes.c_double), ("seed", ctypes.c_uint64), ("step", ctypes.c_uint32),
+                ("rollout_id_base", ctypes.c_int32), ("d_scheme_per_rollout", ctypes.c_void_p)]
+
+
+class SelectParams:
+    """Selection parameters of nat_select / nat_compact (see nat_select_params in nat.h)."""
+
+    def __init__(self, scheme, p=1.0, min_cut=1, trunc_frac=1.0, seed=0, step=0, rollout_id_base=0,
+                 scheme_per_rollout=None):
+        self.scheme, self.p, self.min_cut, self.trunc_frac = scheme, p, min_cut, trunc_frac
+        self.seed, self.step, self.rollout_id_base = seed, step, rollout_id_base
+        self.scheme_per_rollout = scheme_per_rollout      # int32 device tensor [B] or None
+
+    def _c(self):
+        spr = self.scheme_per_rollout
+        if spr is not None:
+            _check(spr, torch.int32, "scheme_per_rollout")
+        return _CSelectParams(int(self.scheme), int(self.min_cut), float(self.p), float(self.trunc_frac),
+                              int(self.seed) & (2 ** 64 - 1), int(self.step) & 0xFFFFFFFF, int(self.rollout_id_base),
+                              spr.data_ptr() if spr is not None else None)
+
+
+def library_path():
+    return os.path.join(_PKG_DIR, _LIB_NAME)
+
+
+def load_library():
+    """Load the built library; raises if it has not been built (no fallback exists)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    path = library_path()
+    if not os.path.exists(path):
+        raise FileNotFoundError(f"{path} is missing: build it with `python -m paper_2603_06619_amd.build`")
+    lib = ctypes.CDLL(path)
+    vp, i32, i64, f32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_float, ctypes.c_size_t
+    pp = ctypes.POINTER(_CSelectParams)
+    lib.nat_status_string.restype = ctypes.c_char_p
+    lib.nat_status_string.argtypes = [i32]
+    lib.nat_mask_words.restype = i64
+    lib.nat_mask_words.argtypes = [i64]
+    lib.nat_advantage.restype = i32
+    lib.nat_advantage.argtypes = [vp, i32, i32, f32, vp, vp]
+    lib.nat_select.restype = i32
+    lib.nat_select.argtypes = [pp, vp, i32, i64, vp, vp, vp]
+    lib.nat_compact_workspace_bytes.restype = sz
+    lib.nat_compact_workspace_bytes.argtypes = [i64]
+    lib.nat_compact.restype = i32
+    lib.nat_compact.argtypes = [pp, i32, vp, vp, i32, i64, vp, vp, vp, vp, vp, vp, vp, vp, i32, i32,
+                                vp, vp, vp, vp, vp, sz, vp]
+    for name in ("nat_loss_workspace_bytes", "nat_loss_workspace_min_bytes"):
+        getattr(lib, name).restype = sz
+        getattr(lib, name).argtypes = [i32, i32, i32, i32]
+    lib.nat_loss_fwd_bwd.restype = i32
+    lib.nat_loss_fwd_bwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, f32, f32, f32,
+                                     vp, vp, vp, vp, i32, vp, sz, vp]
+    lib.nat_profile_num_classes.restype = i32
+    lib.nat_profile_class_name.restype = ctypes.c_char_p
+    lib.nat_profile_class_name.argtypes = [i32]
+    lib.nat_profile_enable.restype = i32
+    lib.nat_profile_enable.argtypes = [i32]
+    lib.nat_profile_collect.restype = i32
+    lib.nat_profile_collect.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i64), i32]
+    _lib = lib
+    return lib
+
+
+def status_string(status):
+    return load_library().nat_status_string(int(status)).decode()
+
+
+def _check(t, dtype, name):
+    if not isinstance(t, torch.Tensor) or t.dtype != dtype or not t.is_contiguous():
+        raise TypeError(f"{name}: expected a contiguous {dtype} tensor")
+    return t
+
+
+def _ptr(t):
+    return None if t is None else t.data_ptr()
+
+
+def _stream():
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _raise(status, where):
+    if status != 0:
+        raise NatError(status, where)
+
+
+def _dtype_code(t):
+    if t.dtype == torch.float32:
+        return DTYPE_F32
+    if t.dtype == torch.bfloat16:
+        return DTYPE_BF16
+    raise TypeError("hidden / W must be float32 or bfloat16")
+
+
+def mask_words(N):
+    return int(load_library().nat_mask_words(int(N)))
+
+
+def compact_workspace_bytes(N):
+    return int(load_library().nat_compact_workspace_bytes(int(N)))
+
+
+def loss_workspace_bytes(N_k, H, V, dtype):
+    return int(load_library().nat_loss_workspace_bytes(int(N_k), int(H), int(V), int(dtype)))
+
+
+def loss_workspace_min_bytes(N_k, H, V, dtype):
+    return int(load_library().nat_loss_workspace_min_bytes(int(N_k), int(H), int(V), int(dtype)))
+
+
+def nat_advantage(rewards, P, G, eps_adv, adv_out):
+    _check(rewards, torch.float32, "rewards")
+    _check(adv_out, torch.float32, "adv_out")
+    _raise(load_library().nat_advantage(_ptr(rewards), P, G, eps_adv, _ptr(adv_out), _stream()), "nat_advantage")
+
+
+def nat_select(params, cu_seqlens, B, N, cut_len_out, mask_bits_out):
+    _check(cu_seqlens, torch.int64, "cu_seqlens")
+    _check(cut_len_out, torch.int32, "cut_len_out")
+    _check(mask_bits_out, torch.int32, "mask_bits_out")
+    c = params._c()
+    _raise(load_library().nat_select(ctypes.byref(c), _ptr(cu_seqlens), B, N, _ptr(cut_len_out),
+                                     _ptr(mask_bits_out), _stream()), "nat_select")
+
+
+def nat_compact(params, n_rollouts_global, mask_bits, cu_seqlens, B, N, kept_idx, kept_seq, kept_w, cu_kept,
+                n_kept, h_n_kept, workspace, hidden=None, hidden_k=None, ids=None, ids_k=None,
+                old_logp=None, old_logp_k=None):
+    c = params._c()
+    H = hidden.shape[1] if hidden is not None else 0
+    dt = _dtype_code(hidden) if hidden is not None else DTYPE_F32
+    _raise(load_library().nat_compact(
+        ctypes.byref(c), n_rollouts_global, _ptr(mask_bits), _ptr(cu_seqlens), B, N, _ptr(kept_idx), _ptr(kept_seq),
+        _ptr(kept_w), _ptr(cu_kept), _ptr(n_kept), _ptr(h_n_kept), _ptr(hidden), _ptr(hidden_k), H, dt,
+        _ptr(ids), _ptr(ids_k), _ptr(old_logp), _ptr(old_logp_k), _ptr(workspace),
+        workspace.numel() * workspace.element_size() if workspace is not None else 0, _stream()), "nat_compact")
+
+
+def nat_loss_fwd_bwd(hidden_k, W, ids_k, old_logp_k, adv, kept_seq, kept_w, N_k, eps_lo, eps_hi, grad_scale,
+                     loss_out, logp_out, dH_out, dW_out, accumulate_dw, workspace):
+    V, H = W.shape
+    _raise(load_library().nat_loss_fwd_bwd(
+        _ptr(hidden_k), _ptr(W), _ptr(ids_k), _ptr(old_logp_k), _ptr(adv), _ptr(kept_seq), _ptr(kept_w),
+        N_k, H, V, _dtype_code(W), eps_lo, eps_hi, grad_scale, _ptr(loss_out), _ptr(logp_out), _ptr(dH_out),
+        _ptr(dW_out), int(accumulate_dw), _ptr(workspace),
+        workspace.numel() * workspace.element_size() if workspace is not None else 0, _stream()), "nat_loss_fwd_bwd")
+
+
+def profile_enable(on):
+    _raise(load_library().nat_profile_enable(int(bool(on))), "nat_profile_enable")
+
+
+def profile_collect():
+    """Returns {class name: (milliseconds, launches)} accumulated since the last call."""
+    lib = load_library()
+    n = lib.nat_profile_num_classes()
+    ms = (ctypes.c_double * n)()
+    cnt = (ctypes.c_int64 * n)()
+    _raise(lib.nat_profile_collect(ms, cnt, n), "nat_profile_collect")
+    return {lib.nat_profile_class_name(i).decode(): (ms[i], cnt[i]) for i in range(n)}

@@ -1,0 +1,42 @@
+// Per-token scalar part of the loss (Eq. 1, Eq. 3) and the fixed-order loss
+// reduction, shared by the bf16 and fp32 paths.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace nat {
+
+struct TokenScalars { float S; float c; };
+
+// r = exp(logp - old_logp); S = min(r A, clip(r, 1-eps_lo, 1+eps_hi) A);
+// dS/dlogp = r A on the unclipped branch (boundaries inclusive), else 0;
+// c = dLoss/dlogp = -grad_scale * w * dS/dlogp.
+__device__ __forceinline__ TokenScalars grpo_token_scalars(float logp, float old_logp, float A, float w,
+                                                           float eps_lo, float eps_hi, float grad_scale) {
+  const float r = expf(logp - old_logp);
+  const float r_clip = fminf(fmaxf(r, 1.f - eps_lo), 1.f + eps_hi);
+  const float S = fminf(r * A, r_clip * A);
+  const bool active = (A > 0.f && r <= 1.f + eps_hi) || (A < 0.f && r >= 1.f - eps_lo);
+  TokenScalars out;
+  out.S = S;
+  out.c = active ? -grad_scale * w * (r * A) : 0.f;
+  return out;
+}
+
+// loss = -sum_k term[k], one block, fixed order: lane-strided fp64 partial sums,
+// then a fixed binary tree over the 1024 partials.
+static __global__ void __launch_bounds__(1024)
+loss_reduce_kernel(const float* __restrict__ term, int n, float* __restrict__ loss) {
+  __shared__ double part[1024];
+  double s = 0.0;
+  for (int k = threadIdx.x; k < n; k += 1024) s += (double)term[k];
+  part[threadIdx.x] = s;
+  __syncthreads();
+  for (int half = 512; half > 0; half >>= 1) {
+    if ((int)threadIdx.x < half) part[threadIdx.x] += part[threadIdx.x + half];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) *loss = (float)(-part[0]);
+}
+
+}  // namespace nat

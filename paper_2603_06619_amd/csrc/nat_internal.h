@@ -1,0 +1,52 @@
+// Internal declarations shared by the library's translation units (not installed).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+#include "nat.h"
+
+namespace nat {
+
+// Kernel classes for the optional per-kernel timing.
+enum ProfClass : int {
+  PC_ADVANTAGE = 0, PC_SELECT, PC_COMPACT, PC_GATHER, PC_TRANSPOSE, PC_LOGITS, PC_TOKEN_STATS,
+  PC_RESCALE, PC_DHIDDEN, PC_DWEIGHT, PC_LOSS_REDUCE, PC_F32_PATH, PC_FILL, PC_NUM
+};
+
+// Brackets the launches issued during its lifetime with two events when timing is on.
+struct ProfScope {
+  ProfScope(int cls, hipStream_t s);
+  ~ProfScope();
+  int cls_; hipStream_t s_; void* rec_;
+};
+
+inline nat_status hip_status(hipError_t e) { return e == hipSuccess ? NAT_OK : NAT_HIP_ERROR; }
+#define NAT_HIP_TRY(expr) do { hipError_t e__ = (expr); if (e__ != hipSuccess) return NAT_HIP_ERROR; } while (0)
+#define NAT_LAUNCH_CHECK() do { hipError_t e__ = hipGetLastError(); if (e__ != hipSuccess) return NAT_HIP_ERROR; } while (0)
+
+// Validated host-side copy of the selection parameters handed to kernels by value.
+struct SelectArgs {
+  int32_t scheme; int32_t min_cut; double p; double trunc_frac;
+  uint64_t urs_threshold;       // floor(p * 2^32)
+  uint32_t key0, key1, step; int32_t rollout_id_base;
+  const int32_t* scheme_per_rollout;
+};
+nat_status validate_select(const nat_select_params* p, SelectArgs* out);
+
+// bf16 loss path (loss_bf16.hip) and fp32 loss path (loss_f32.hip)
+struct LossArgs {
+  const void* hidden; const void* W; const int32_t* ids; const float* old_logp; const float* adv;
+  const int32_t* kept_seq; const float* kept_w; int32_t N_k, H, V;
+  float eps_lo, eps_hi, grad_scale;
+  float* loss; float* logp; void* dH; float* dW; int32_t accumulate_dw;
+  void* ws; size_t ws_bytes; hipStream_t stream;
+};
+size_t loss_bf16_workspace_bytes(int32_t N_k, int32_t H, int32_t V, bool minimal);
+nat_status loss_bf16_run(const LossArgs& a);
+size_t loss_f32_workspace_bytes(int32_t N_k, int32_t H, int32_t V, bool minimal);
+nat_status loss_f32_run(const LossArgs& a);
+
+// shared small kernels (api.hip)
+nat_status fill_zero_f32(float* p, size_t n, hipStream_t s);
+
+}  // namespace nat

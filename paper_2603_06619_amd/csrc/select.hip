@@ -1,0 +1,142 @@
+// nat_advantage and nat_select: group-relative advantage (Eq. 2) and the token
+// selection mask of Sec. 3.1 (URS) and Sec. 4 (RPC, Eq. 7; deterministic
+// truncation).  One lane per packed token position; a wavefront ballot packs
+// 64 mask bits into two 32-bit words.
+#include "nat_internal.h"
+#include "philox.hip.h"
+
+namespace nat {
+
+// Rollout that contains packed position n: the last i with cu[i] <= n (skips
+// empty rollouts, whose offsets repeat).
+__device__ __forceinline__ int rollout_of(const int64_t* __restrict__ cu, int B, int64_t n) {
+  int lo = 0, hi = B;              // invariant: cu[lo] <= n < cu[hi]
+  while (hi - lo > 1) {
+    const int mid = (lo + hi) >> 1;
+    if (cu[mid] <= n) lo = mid; else hi = mid;
+  }
+  return lo;
+}
+
+__global__ void advantage_kernel(const float* __restrict__ rewards, int P, int G, float eps_adv,
+                                 float* __restrict__ adv) {
+  // one wavefront per prompt; fixed-order lane-strided sums then a butterfly
+  const int prompt = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+  const int lane = threadIdx.x & 63;
+  if (prompt >= P) return;
+  const float* R = rewards + (size_t)prompt * G;
+  float s = 0.f;
+  for (int j = lane; j < G; j += 64) s += R[j];
+  for (int off = 32; off > 0; off >>= 1) s += __shfl_xor(s, off);
+  const float mu = s / (float)G;
+  float q = 0.f;
+  for (int j = lane; j < G; j += 64) { const float d = R[j] - mu; q += d * d; }
+  for (int off = 32; off > 0; off >>= 1) q += __shfl_xor(q, off);
+  const float sigma = sqrtf(q / (float)G);
+  for (int j = lane; j < G; j += 64) adv[(size_t)prompt * G + j] = (R[j] - mu) / (sigma + eps_adv);
+}
+
+// cut_len[i] = L_i (RPC), K_i (DET), T_i (FULL, URS)
+__global__ void select_cut_kernel(SelectArgs a, const int64_t* __restrict__ cu, int B,
+                                  int32_t* __restrict__ cut_len) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= B) return;
+  const int64_t T = cu[i + 1] - cu[i];
+  const int scheme = a.scheme_per_rollout ? a.scheme_per_rollout[i] : a.scheme;
+  int64_t cut = T;
+  if (T > 0 && scheme == NAT_SCHEME_RPC) {
+    int64_t Ci = a.min_cut < 1 ? 1 : a.min_cut;
+    if (Ci > T) Ci = T;
+    const uint64_t n = (uint64_t)(T - Ci + 1);
+    const u32x4 r = philox4x32_10(u32x4{0u, (uint32_t)(a.rollout_id_base + i), 1u, a.step}, a.key0, a.key1);
+    cut = Ci + (int64_t)(((uint64_t)r.x * n) >> 32);
+  } else if (scheme == NAT_SCHEME_DET) {
+    cut = (int64_t)floor(a.trunc_frac * (double)T);
+  }
+  cut_len[i] = (int32_t)cut;
+}
+
+__global__ void __launch_bounds__(256)
+select_mask_kernel(SelectArgs a, const int64_t* __restrict__ cu, int B, int64_t N,
+                   const int32_t* __restrict__ cut_len, uint32_t* __restrict__ mask_bits) {
+  const int64_t n = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  bool keep = false;
+  if (n < N) {
+    const int i = rollout_of(cu, B, n);
+    const int64_t t0 = n - cu[i];
+    const int scheme = a.scheme_per_rollout ? a.scheme_per_rollout[i] : a.scheme;
+    if (scheme == NAT_SCHEME_URS) {
+      const u32x4 r = philox4x32_10(u32x4{(uint32_t)(t0 >> 2), (uint32_t)(a.rollout_id_base + i), 0u, a.step},
+                                    a.key0, a.key1);
+      const uint32_t lane_word = (t0 & 3) == 0 ? r.x : (t0 & 3) == 1 ? r.y : (t0 & 3) == 2 ? r.z : r.w;
+      keep = (uint64_t)lane_word < a.urs_threshold;
+    } else if (scheme == NAT_SCHEME_FULL) {
+      keep = true;
+    } else {
+      keep = t0 < (int64_t)cut_len[i];
+    }
+  }
+  const uint64_t ballot = __ballot(keep);
+  // groups past ceil(N/64) have no words in the mask (the last block may hold some)
+  if ((threadIdx.x & 63) == 0 && n < N) {
+    const int64_t group = n >> 6;
+    mask_bits[2 * group] = (uint32_t)ballot;
+    mask_bits[2 * group + 1] = (uint32_t)(ballot >> 32);
+  }
+}
+
+nat_status validate_select(const nat_select_params* p, SelectArgs* out) {
+  if (!p) return NAT_INVALID_ARG;
+  if (p->scheme < NAT_SCHEME_FULL || p->scheme > NAT_SCHEME_DET) return NAT_INVALID_ARG;
+  if (!(p->p > 0.0 && p->p <= 1.0)) return NAT_INVALID_ARG;
+  if (p->min_cut < 1) return NAT_INVALID_ARG;
+  if (!(p->trunc_frac > 0.0 && p->trunc_frac <= 1.0)) return NAT_INVALID_ARG;
+  out->scheme = p->scheme;
+  out->min_cut = p->min_cut;
+  out->p = p->p;
+  out->trunc_frac = p->trunc_frac;
+  out->urs_threshold = (uint64_t)floor(p->p * 4294967296.0);
+  out->key0 = (uint32_t)(p->seed & 0xFFFFFFFFull);
+  out->key1 = (uint32_t)(p->seed >> 32);
+  out->step = p->step;
+  out->rollout_id_base = p->rollout_id_base;
+  out->scheme_per_rollout = p->d_scheme_per_rollout;
+  return NAT_OK;
+}
+
+}  // namespace nat
+
+using namespace nat;
+
+extern "C" nat_status nat_advantage(const float* d_rewards, int32_t P, int32_t G, float eps_adv,
+                                    float* d_adv, void* stream) {
+  if (!d_rewards || !d_adv || P <= 0 || G <= 0 || !(eps_adv >= 0.f)) return NAT_INVALID_ARG;
+  hipStream_t s = (hipStream_t)stream;
+  ProfScope prof(PC_ADVANTAGE, s);
+  const int waves_per_block = 4;
+  advantage_kernel<<<(P + waves_per_block - 1) / waves_per_block, 64 * waves_per_block, 0, s>>>(
+      d_rewards, P, G, eps_adv, d_adv);
+  NAT_LAUNCH_CHECK();
+  return NAT_OK;
+}
+
+extern "C" int64_t nat_mask_words(int64_t N) { return N <= 0 ? 0 : 2 * ((N + 63) / 64); }
+
+extern "C" nat_status nat_select(const nat_select_params* params, const int64_t* d_cu_seqlens, int32_t B,
+                                 int64_t N, int32_t* d_cut_len, uint32_t* d_mask_bits, void* stream) {
+  SelectArgs a;
+  nat_status st = validate_select(params, &a);
+  if (st != NAT_OK) return st;
+  if (!d_cu_seqlens || !d_cut_len || B <= 0 || N < 0 || N >= (int64_t(1) << 31)) return NAT_INVALID_ARG;
+  if (N > 0 && !d_mask_bits) return NAT_INVALID_ARG;
+  hipStream_t s = (hipStream_t)stream;
+  ProfScope prof(PC_SELECT, s);
+  select_cut_kernel<<<(B + 255) / 256, 256, 0, s>>>(a, d_cu_seqlens, B, d_cut_len);
+  NAT_LAUNCH_CHECK();
+  if (N > 0) {
+    const int64_t blocks = (N + 255) / 256;
+    select_mask_kernel<<<(unsigned)blocks, 256, 0, s>>>(a, d_cu_seqlens, B, N, d_cut_len, d_mask_bits);
+    NAT_LAUNCH_CHECK();
+  }
+  return NAT_OK;
+}

@@ -1,0 +1,115 @@
+"""Host-only checks of the C-ABI library: it loads, exports every symbol that
+include/nat.h declares, and rejects bad arguments before launching anything."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    import paper_2603_06619_amd as nat
+    if not os.path.exists(nat.library_path()):
+        from paper_2603_06619_amd import build
+        build.build()
+    return nat.load_library()
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "nat.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(nat_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = declared_functions()
+    assert {"nat_advantage", "nat_select", "nat_compact", "nat_loss_fwd_bwd", "nat_status_string",
+            "nat_loss_workspace_bytes", "nat_compact_workspace_bytes"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_status_strings(lib):
+    assert lib.nat_status_string(0) == b"NAT_OK"
+    assert lib.nat_status_string(3) == b"NAT_WORKSPACE_TOO_SMALL"
+    assert lib.nat_status_string(77) == b"NAT_UNKNOWN_STATUS"
+
+
+def test_size_queries(lib):
+    assert lib.nat_mask_words(0) == 0 and lib.nat_mask_words(1) == 2 and lib.nat_mask_words(64) == 2
+    assert lib.nat_mask_words(65) == 4
+    assert lib.nat_compact_workspace_bytes(1 << 20) >= (2 * 256 + 1) * 4
+    big = lib.nat_loss_workspace_bytes(100000, 4096, 151936, 1)
+    small = lib.nat_loss_workspace_min_bytes(100000, 4096, 151936, 1)
+    assert 0 < small < big < 16 * 2 ** 30
+    assert lib.nat_loss_workspace_bytes(10, 100, 512, 1) == 0          # bf16 needs H % 64 == 0
+    assert lib.nat_loss_workspace_bytes(10, 64, 512, 0) > 0
+    assert lib.nat_loss_workspace_bytes(10, 64, 512, 9) == 0
+
+
+def _params(nat, **kw):
+    from paper_2603_06619_amd.binding import _CSelectParams
+    d = dict(scheme=1, min_cut=1, p=0.5, trunc_frac=0.5, seed=1, step=0, rollout_id_base=0, d_scheme_per_rollout=None)
+    d.update(kw)
+    return _CSelectParams(**d)
+
+
+def test_select_argument_errors(lib):
+    import paper_2603_06619_amd as nat
+    fake = ctypes.c_void_p(256)           # never dereferenced: all of these fail validation first
+    ok = _params(nat)
+    assert lib.nat_select(None, fake, 4, 10, fake, fake, None) == 1
+    assert lib.nat_select(ctypes.byref(ok), None, 4, 10, fake, fake, None) == 1
+    assert lib.nat_select(ctypes.byref(ok), fake, 0, 10, fake, fake, None) == 1
+    assert lib.nat_select(ctypes.byref(ok), fake, 4, -1, fake, fake, None) == 1
+    assert lib.nat_select(ctypes.byref(ok), fake, 4, 1 << 31, fake, fake, None) == 1
+    for bad in (dict(p=0.0), dict(p=1.5), dict(min_cut=0), dict(trunc_frac=0.0), dict(trunc_frac=2.0),
+                dict(scheme=4), dict(scheme=-1), dict(p=float("nan"))):
+        assert lib.nat_select(ctypes.byref(_params(nat, **bad)), fake, 4, 10, fake, fake, None) == 1, bad
+
+
+def test_compact_argument_errors(lib):
+    import paper_2603_06619_amd as nat
+    fake = ctypes.c_void_p(256)
+    ok = ctypes.byref(_params(nat))
+    args = lambda **kw: [kw.get("params", ok), kw.get("nroll", 4), fake, fake, kw.get("B", 4), kw.get("N", 100),
+                         fake, fake, fake, fake, fake, None,
+                         kw.get("hidden", None), kw.get("hidden_k", None), kw.get("H", 0), kw.get("dtype", 0),
+                         None, None, None, None, kw.get("ws", fake), kw.get("ws_bytes", 1 << 20), None]
+    assert lib.nat_compact(*args(nroll=0)) == 1
+    assert lib.nat_compact(*args(B=0)) == 1
+    assert lib.nat_compact(*args(hidden=fake)) == 1                       # gather pair incomplete
+    assert lib.nat_compact(*args(hidden=fake, hidden_k=fake, H=3, dtype=1)) == 2   # row not 16-byte multiple
+    assert lib.nat_compact(*args(hidden=fake, hidden_k=fake, H=64, dtype=5)) == 4
+    assert lib.nat_compact(*args(ws_bytes=8)) == 3
+    assert lib.nat_compact(*args(ws=None)) == 3
+
+
+def test_loss_argument_errors(lib):
+    fake = ctypes.c_void_p(256)
+    f = ctypes.c_float
+    def call(N_k=10, H=64, V=512, dtype=1, eps=0.2, hidden=fake, W=fake, ws=fake, ws_bytes=1 << 34):
+        return lib.nat_loss_fwd_bwd(hidden, W, fake, fake, fake, fake, fake, N_k, H, V, dtype, f(eps), f(eps), f(1.0),
+                                    fake, None, fake, fake, 0, ws, ws_bytes, None)
+    assert call(dtype=7) == 4
+    assert call(N_k=-1) == 1
+    assert call(eps=-0.1) == 1
+    assert call(H=0) == 2 and call(V=0) == 2
+    assert call(H=100) == 2                      # bf16 kernels need H % 64 == 0
+    assert call(W=None) == 1
+    assert call(hidden=None) == 1
+    assert call(ws_bytes=1024) == 3
+    assert call(ws=None) == 3
+
+
+def test_profile_interface(lib):
+    n = lib.nat_profile_num_classes()
+    names = [lib.nat_profile_class_name(i) for i in range(n)]
+    assert b"logits_gemm" in names and b"dweight_gemm" in names and len(set(names)) == n
+    ms = (ctypes.c_double * n)()
+    cnt = (ctypes.c_int64 * n)()
+    assert lib.nat_profile_collect(ms, cnt, n) == 0 and sum(cnt) == 0
+    assert lib.nat_profile_collect(ms, cnt, 1) == 1

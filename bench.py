@@ -1,0 +1,182 @@
+#!/usr/bin/env python3
+"""Benchmark of the partial-token GRPO loss stage on one MI355X.
+
+One step = one pass of the whole hot path over one synthetic batch that is
+already resident in HBM: nat_advantage -> nat_select -> nat_compact (with the
+gather of kept rows) -> nat_loss_fwd_bwd.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--scheme rpc|urs|full|det]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA peak
+METRIC = "kept tokens/sec fused fwd+bwd at Qwen3-8B head shape; MFMA util % of bf16 peak"
+GEMM_CLASSES = ("logits_gemm", "dhidden_gemm", "dweight_gemm")
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--workload", default="qwen3_8b_head_rpc")
+    ap.add_argument("--scheme", default=None, help="rpc | urs | full | det (default: the workload's own)")
+    ap.add_argument("--p", type=float, default=0.5)
+    ap.add_argument("--min-cut", type=int, default=1)
+    ap.add_argument("--seed", type=int, default=2000)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--prompts", type=int, default=None, help="override the number of prompts (smaller batch)")
+    return ap.parse_args()
+
+
+def cpu_baseline(batch, old_logp, scheme_code, args, torch):
+    """The fp64 oracle, timed on the host on a bounded sample of the same batch: the first
+    rollouts, each truncated to at most 48 tokens, through select -> compact -> loss."""
+    import numpy as np
+    from threadpoolctl import threadpool_info
+    from oracle import grpo as ogrpo
+    from oracle import select as osel
+
+    max_rollouts, max_len = 4, 48
+    cu_full = batch["cu_seqlens"]
+    rows, lens = [], []
+    for i in range(min(max_rollouts, batch["B"])):
+        T = int(min(max_len, cu_full[i + 1] - cu_full[i]))
+        rows.append(np.arange(cu_full[i], cu_full[i] + T))
+        lens.append(T)
+    rows = np.concatenate(rows)
+    cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+    ridx = torch.from_numpy(rows).to(batch["hidden"].device)
+    hidden = batch["hidden"][ridx].float().cpu().numpy()
+    ids = batch["ids"][ridx].cpu().numpy()
+    old = old_logp[ridx].cpu().numpy()
+    W = batch["W"].float().cpu().numpy()
+    R = batch["rewards"]
+    t0 = time.perf_counter()
+    adv = ogrpo.advantages(R).reshape(-1)[:len(lens)]
+    d = osel.select(cu, scheme_code, p=args.p, C=args.min_cut, beta=0.5, seed=args.seed, step=0)
+    c = osel.compact(d["mask"], cu, len(lens), scheme_code, p=args.p, C=args.min_cut)
+    k = c["kept_idx"]
+    out = ogrpo.loss_and_grads(hidden[k], W, ids[k], old[k], adv[c["kept_seq"]], c["kept_w"].astype(np.float64))
+    dt = time.perf_counter() - t0
+    threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    return dict(value=c["n_kept"] / dt, unit="kept tokens/s", cores=int(threads), kind="oracle",
+                sample=f"first {len(lens)} rollouts truncated to <= {max_len} tokens ({int(cu[-1])} tokens, "
+                       f"{c['n_kept']} kept) at the full head shape, fp64 numpy, {dt:.1f} s",
+                loss=out["loss"])
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print(f"bench.py measures one GPU only (got --gpus {args.gpus}); the path shards by rollout, "
+              "see DESIGN.md", file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+    import synth_inputs as si
+    import paper_2603_06619_amd as nat
+    from paper_2603_06619_amd.stage import LossStage
+
+    if not os.path.exists(nat.library_path()):
+        from paper_2603_06619_amd import build
+        build.build()
+    nat.load_library()
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    stage = LossStage(dev)
+
+    default_scheme = {"qwen3_8b_head_rpc": "rpc", "qwen3_0p6b_head": "urs", "qwen3_8b_long_cot": "urs",
+                      "wide_head_stress": "urs", "tiny_fp32": "urs"}[args.workload]
+    scheme_name = args.scheme or default_scheme
+    scheme_code = dict(full=nat.FULL, urs=nat.URS, rpc=nat.RPC, det=nat.DET)[scheme_name]
+
+    batch = si.make_batch_torch(args.workload, args.seed, dev, P=args.prompts)
+    P, G, B, N, H, V = batch["P"], batch["G"], batch["B"], batch["N"], batch["H"], batch["V"]
+    old_logp = si.behaviour_logp_stand_in(batch["hidden"], batch["W"], batch["ids"], batch["logp_noise"])
+    rewards = torch.from_numpy(batch["rewards"].reshape(-1)).to(dev)
+    cu = torch.from_numpy(batch["cu_seqlens"]).to(dev)
+    params = nat.SelectParams(scheme_code, p=args.p, min_cut=args.min_cut, trunc_frac=0.5, seed=args.seed, step=0)
+    dW = torch.empty((V, H), dtype=torch.float32, device=dev)
+    dtype_code = nat.DTYPE_BF16 if batch["dtype"] == "bf16" else nat.DTYPE_F32
+
+    def step(step_no):
+        params.step = step_no
+        adv = stage.advantage(rewards, P, G)
+        sc = stage.select_compact(params, cu, B, N, hidden=batch["hidden"], ids=batch["ids"], old_logp=old_logp)
+        nk = sc["n_kept"]
+        out = stage.loss(sc["hidden_k"], batch["W"], sc["ids_k"], sc["old_logp_k"], adv, sc["kept_seq"], sc["kept_w"],
+                         nk, dW=dW, want_logp=True)
+        return nk, out
+
+    for w in range(args.warmup):
+        step(w)
+    torch.cuda.synchronize()
+    nat.profile_collect()
+    nat.profile_enable(True)
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    kept_total = 0
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    ev0.record()
+    for s in range(args.steps):
+        nk, out = step(args.warmup + s)
+        kept_total += nk
+    ev1.record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    nat.profile_enable(False)
+    prof = nat.profile_collect()
+    ms_total = ev0.elapsed_time(ev1)
+    ms_per_step = wall * 1e3 / args.steps
+    value = kept_total / wall
+
+    # roofline of the dominant kernel: algorithmic flops = 2*V*H per kept token for each of the
+    # three contractions; every kept token passes through each GEMM class exactly once per step
+    flops_per_class = 2.0 * V * H * kept_total
+    dom = max(GEMM_CLASSES, key=lambda c: prof[c][0]) if dtype_code == nat.DTYPE_BF16 else "f32_path"
+    dom_ms, dom_launches = prof[dom]
+    if dtype_code == nat.DTYPE_BF16:
+        achieved = flops_per_class / (dom_ms * 1e-3) / 1e12
+        roofline = dict(bound="mfma", kernel=dom, achieved=achieved, peak=PEAK_BF16_TFLOPS, unit="TFLOP/s",
+                        frac=achieved / PEAK_BF16_TFLOPS, traffic=None,
+                        avg_launch_ms=dom_ms / max(dom_launches, 1), launches=int(dom_launches))
+    else:
+        achieved = 3 * flops_per_class / (dom_ms * 1e-3) / 1e12
+        roofline = dict(bound="alu", kernel=dom, achieved=achieved, peak=157.3, unit="TFLOP/s",
+                        frac=achieved / 157.3, traffic=None, avg_launch_ms=dom_ms / max(dom_launches, 1),
+                        launches=int(dom_launches))
+    kernels = {k: dict(ms_per_step=v[0] / args.steps, launches_per_step=v[1] / args.steps)
+               for k, v in prof.items() if v[1] > 0}
+    gemm_ms = sum(prof[c][0] for c in GEMM_CLASSES)
+    useful_tflops = 6.0 * V * H * kept_total / wall / 1e12
+
+    result = {
+        "metric": METRIC, "value": value, "unit": "kept tokens/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": batch["dtype"], "data": "synthetic",
+        "config": {"workload": args.workload, "P": P, "G": G, "H": H, "V": V, "tokens": N,
+                   "kept_tokens_per_step": kept_total / args.steps, "scheme": scheme_name,
+                   "p": args.p if scheme_name == "urs" else None, "min_cut": args.min_cut if scheme_name == "rpc" else None},
+        "mfma_util_pct_useful_6VH": 100.0 * useful_tflops / PEAK_BF16_TFLOPS,
+        "mfma_util_pct_gemm_kernels_only": (100.0 * 6.0 * V * H * kept_total / (gemm_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS
+                                            if gemm_ms > 0 else None),
+        "gpu_event_ms_per_step": ms_total / args.steps,
+        "loss": float(out["loss"].item()),
+        "roofline": roofline,
+        "kernels": kernels,
+    }
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(batch, old_logp, scheme_code, args, torch)
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

@@ -85,27 +85,38 @@ __device__ __forceinline__ void tile_of_block(const GemmArgs& g, int& tm, int& t
 // 16-byte chunk c of row r of a [256][64] bf16 tile; XOR swizzle against bank conflicts.
 __device__ __forceinline__ int lds_chunk_off(int r, int c) { return r * (kBK * 2) + ((c ^ (r & 7)) << 4); }
 
-struct StageRegs { uint4 a[8]; uint4 b[8]; };
+// Global -> LDS copy of one [256][64] bf16 operand tile without staging registers:
+// each wavefront issues 8 direct-to-LDS loads of 16 bytes per lane.  One instruction
+// fills 8 consecutive tile rows (1 KiB); the hardware places lane l at byte 16*l of
+// that block, so the swizzle is applied by choosing which 16-byte chunk of the row
+// each lane fetches: lane l -> row l/8, logical chunk (l%8) ^ (l/8).
+struct TileLoader {
+  const uint16_t* rowp[8];       // per-lane source pointer of each of the 8 loads (k = 0)
 
-__device__ __forceinline__ void load_stage(const GemmArgs& g, int m0, int n0, int k0, StageRegs& st) {
+  __device__ __forceinline__ void init(const uint16_t* base, int64_t ld, int row0, int n_rows, int wave, int lane) {
 #pragma unroll
-  for (int j = 0; j < 8; ++j) {
-    const int q = j * kThreads + threadIdx.x;
-    const int row = q >> 3, chunk = q & 7;
-    int ra = m0 + row; ra = ra < g.M ? ra : g.M - 1;
-    int rb = n0 + row; rb = rb < g.N ? rb : g.N - 1;
-    st.a[j] = *(const uint4*)(g.A + (int64_t)ra * g.lda + k0 + chunk * 8);
-    st.b[j] = *(const uint4*)(g.B + (int64_t)rb * g.ldb + k0 + chunk * 8);
+    for (int j = 0; j < 8; ++j) {
+      int r = row0 + (j * 4 + wave) * 8 + (lane >> 3);
+      r = r < n_rows ? r : n_rows - 1;
+      rowp[j] = base + (int64_t)r * ld + (((lane & 7) ^ (lane >> 3)) << 3);
+    }
   }
-}
-
-__device__ __forceinline__ void store_stage(char* ldsA, char* ldsB, const StageRegs& st) {
+  __device__ __forceinline__ void issue(char* lds_tile, int k0, int wave) const {
 #pragma unroll
-  for (int j = 0; j < 8; ++j) {
-    const int q = j * kThreads + threadIdx.x;
-    const int off = lds_chunk_off(q >> 3, q & 7);
-    *(uint4*)(ldsA + off) = st.a[j];
-    *(uint4*)(ldsB + off) = st.b[j];
+    for (int j = 0; j < 8; ++j) {
+      __builtin_amdgcn_global_load_lds(
+          (const __attribute__((address_space(1))) void*)(rowp[j] + k0),
+          (__attribute__((address_space(3))) void*)(lds_tile + (j * 4 + wave) * 8 * (kBK * 2)), 16, 0, 0);
+    }
+  }
+};
+
+__device__ __forceinline__ void load_frags(const char* a_s, const char* b_s, int wm, int wn, int l32, int lhi, int ks,
+                                           bf16x8 (&af)[4], bf16x8 (&bfr)[4]) {
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    af[i] = *(const bf16x8*)(a_s + lds_chunk_off(wm * 128 + i * 32 + l32, ks * 2 + lhi));
+    bfr[i] = *(const bf16x8*)(b_s + lds_chunk_off(wn * 128 + i * 32 + l32, ks * 2 + lhi));
   }
 }
 
@@ -113,11 +124,12 @@ __device__ __forceinline__ void store_stage(char* ldsA, char* ldsB, const StageR
 template <class Epilogue>
 __global__ void __launch_bounds__(kThreads, 1)
 gemm_nt_kernel(GemmArgs g, Epilogue epi) {
-  __shared__ __attribute__((aligned(16))) char lds[2][2][kTileBytes];
+  __shared__ __attribute__((aligned(1024))) char lds[2][2][kTileBytes];
   int tm, tn;
   tile_of_block(g, tm, tn);
   const int m0 = tm * kBM, n0 = tn * kBN;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int wm = wave >> 1, wn = wave & 1;
   const int l32 = lane & 31, lhi = lane >> 5;
 
@@ -129,35 +141,35 @@ gemm_nt_kernel(GemmArgs g, Epilogue epi) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-  StageRegs st;
-  load_stage(g, m0, n0, 0, st);
-  store_stage(lds[0][0], lds[0][1], st);
+  TileLoader la, lb;
+  la.init(g.A, g.lda, m0, g.M, wave, lane);
+  lb.init(g.B, g.ldb, n0, g.N, wave, lane);
+  la.issue(lds[0][0], 0, wave);
+  lb.issue(lds[0][1], 0, wave);
+  __builtin_amdgcn_s_waitcnt(0x0f70);        // vmcnt(0): the direct-to-LDS loads have landed
   __syncthreads();
 
   const int kt_n = g.K / kBK;
   for (int kt = 0; kt < kt_n; ++kt) {
     const int cur = kt & 1;
-    const bool more = kt + 1 < kt_n;
-    if (more) load_stage(g, m0, n0, (kt + 1) * kBK, st);
+    if (kt + 1 < kt_n) {
+      la.issue(lds[cur ^ 1][0], (kt + 1) * kBK, wave);
+      lb.issue(lds[cur ^ 1][1], (kt + 1) * kBK, wave);
+    }
     const char* a_s = lds[cur][0];
     const char* b_s = lds[cur][1];
+    bf16x8 af[2][4], bfr[2][4];
+    load_frags(a_s, b_s, wm, wn, l32, lhi, 0, af[0], bfr[0]);
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) {
-      bf16x8 af[4], bfr[4];
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const int ra = wm * 128 + i * 32 + l32;
-        const int rb = wn * 128 + i * 32 + l32;
-        af[i] = *(const bf16x8*)(a_s + lds_chunk_off(ra, ks * 2 + lhi));
-        bfr[i] = *(const bf16x8*)(b_s + lds_chunk_off(rb, ks * 2 + lhi));
-      }
+      if (ks < 3) load_frags(a_s, b_s, wm, wn, l32, lhi, ks + 1, af[(ks + 1) & 1], bfr[(ks + 1) & 1]);
 #pragma unroll
       for (int i = 0; i < 4; ++i)
 #pragma unroll
         for (int j = 0; j < 4; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ks & 1][i], bfr[ks & 1][j], acc[i][j], 0, 0, 0);
     }
-    if (more) store_stage(lds[cur ^ 1][0], lds[cur ^ 1][1], st);
+    __builtin_amdgcn_s_waitcnt(0x0f70);      // vmcnt(0)
     __syncthreads();
   }
   epi(acc, m0 + wm * 128, n0 + wn * 128, lane);

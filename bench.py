@@ -38,13 +38,13 @@ def parse_args():
 
 def cpu_baseline(batch, old_logp, scheme_code, args, torch):
     """The fp64 oracle, timed on the host on a bounded sample of the same batch: the first
-    rollouts, each truncated to at most 48 tokens, through select -> compact -> loss."""
+    rollouts, each truncated to at most 256 tokens, through select -> compact -> loss."""
     import numpy as np
     from threadpoolctl import threadpool_info
     from oracle import grpo as ogrpo
     from oracle import select as osel
 
-    max_rollouts, max_len = 4, 48
+    max_rollouts, max_len = 8, 256
     cu_full = batch["cu_seqlens"]
     rows, lens = [], []
     for i in range(min(max_rollouts, batch["B"])):

@@ -35,7 +35,7 @@ constexpr int kThreads = 256;
 constexpr int kGranule = 128;                     // vocabulary rows per soft-max partial
 constexpr int kTileBytes = kBM * kBK * 2;         // 16 KiB per operand per stage
 constexpr int kLoadsPerWave = 2 * (kTileBytes / 1024) / 4;   // direct-to-LDS loads per wavefront per stage (A and B)
-constexpr int kMaxChunk = 16384;                  // token rows per chunk (recommended workspace)
+constexpr int kMaxChunk = 32768;                  // token rows per chunk (recommended workspace)
 
 __device__ __forceinline__ uint16_t f32_to_bf16_bits(float x) {
   const __bf16 b = (__bf16)x;
@@ -358,6 +358,9 @@ struct DWeightEpilogue {
 };
 
 // ------------------------------------------------- per-token statistics ----
+// 64 tokens per workgroup; the granules of a token are split over 4 wavefronts (granule
+// gi goes to wavefront gi % 4), each keeping a running (max, sum); the four partial pairs
+// are merged in wavefront order, so the result does not depend on timing.
 __global__ void __launch_bounds__(256)
 token_stats_kernel(const float* __restrict__ m_part, const float* __restrict__ s_part, int n_granules, int64_t ld,
                    const float* __restrict__ z_target, int n_valid, int chunk_start,
@@ -366,15 +369,28 @@ token_stats_kernel(const float* __restrict__ m_part, const float* __restrict__ s
                    float eps_lo, float eps_hi, float grad_scale,
                    float* __restrict__ lse_out, float* __restrict__ c_out, float* __restrict__ logp_chunk,
                    float* __restrict__ logp_out, float* __restrict__ term) {
-  const int kk = blockIdx.x * blockDim.x + threadIdx.x;
-  if (kk >= n_valid) return;
-  float m = -INFINITY;
-  for (int gi = 0; gi < n_granules; ++gi) m = fmaxf(m, m_part[(int64_t)gi * ld + kk]);
-  float s = 0.f;
-  for (int gi = 0; gi < n_granules; ++gi) {
-    const float mg = m_part[(int64_t)gi * ld + kk];
-    if (mg != -INFINITY) s += s_part[(int64_t)gi * ld + kk] * __expf(mg - m);
+  __shared__ float m_s[4][64], s_s[4][64];
+  const int t = threadIdx.x & 63, part = threadIdx.x >> 6;
+  const int kk = blockIdx.x * 64 + t;
+  float m = -INFINITY, s = 0.f;
+  if (kk < n_valid) {
+    for (int gi = part; gi < n_granules; gi += 4) {
+      const float mg = m_part[(int64_t)gi * ld + kk];
+      const float sg = s_part[(int64_t)gi * ld + kk];
+      if (mg == -INFINITY) continue;                    // granule entirely beyond the vocabulary
+      if (mg > m) { s = s * __expf(m - mg) + sg; m = mg; }
+      else s += sg * __expf(mg - m);
+    }
   }
+  m_s[part][t] = m;
+  s_s[part][t] = s;
+  __syncthreads();
+  if (part != 0 || kk >= n_valid) return;
+  m = fmaxf(fmaxf(m_s[0][t], m_s[1][t]), fmaxf(m_s[2][t], m_s[3][t]));
+  s = 0.f;
+#pragma unroll
+  for (int q = 0; q < 4; ++q)
+    if (m_s[q][t] != -INFINITY) s += s_s[q][t] * __expf(m_s[q][t] - m);
   const float lse = m + logf(s);
   const float logp = z_target[kk] - lse;
   const int k = chunk_start + kk;
@@ -556,7 +572,7 @@ nat_status loss_bf16_run(const LossArgs& a) {
     }
     {
       ProfScope prof(PC_TOKEN_STATS, s);
-      token_stats_kernel<<<(nv + 255) / 256, 256, 0, s>>>(m_part, s_part, p.n_granules, cap, zt, nv, c0, a.old_logp,
+      token_stats_kernel<<<(nv + 63) / 64, 256, 0, s>>>(m_part, s_part, p.n_granules, cap, zt, nv, c0, a.old_logp,
                                                          a.adv, a.kept_seq, a.kept_w, a.eps_lo, a.eps_hi,
                                                          a.grad_scale, lse, c, logp_chunk, a.logp, term);
       NAT_LAUNCH_CHECK();

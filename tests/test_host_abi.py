@@ -44,7 +44,7 @@ def test_size_queries(lib):
     assert lib.nat_compact_workspace_bytes(1 << 20) >= (2 * 256 + 1) * 4
     big = lib.nat_loss_workspace_bytes(100000, 4096, 151936, 1)
     small = lib.nat_loss_workspace_min_bytes(100000, 4096, 151936, 1)
-    assert 0 < small < big < 16 * 2 ** 30
+    assert 0 < small < big < 32 * 2 ** 30
     assert lib.nat_loss_workspace_bytes(10, 100, 512, 1) == 0          # bf16 needs H % 64 == 0
     assert lib.nat_loss_workspace_bytes(10, 64, 512, 0) > 0
     assert lib.nat_loss_workspace_bytes(10, 64, 512, 9) == 0

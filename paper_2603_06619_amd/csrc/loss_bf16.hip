@@ -3,18 +3,22 @@
 // 6/9) and the gradients dH, dW (App. A) on the kept tokens.
 //
 // Tokens are processed in chunks of at most `cap` rows.  Per chunk:
-//   logits GEMM   Z^T tile = W_tile . H_chunk^T on bf16 MFMA with fp32 accumulators;
-//                 the epilogue never stores Z: per (token, 128-row vocabulary
-//                 granule) it keeps the local max m and sum s of exp(z - m), the
-//                 target logit, and stores E = exp(z - m) as bf16 (soft-max
-//                 numerators, relative precision preserved);
-//   token stats   merge (m, s) over granules -> log-sum-exp, log-prob, ratio,
-//                 clipped surrogate, c_k = dLoss/dlogp_k;
-//   rescale       dZ = -c_k exp(m - lse_k) E, one-hot term applied in fp32 before
-//                 rounding; written in both orientations;
-//   dH GEMM       dH_chunk = dZ . W           (contraction over the vocabulary);
-//   dW GEMM       dW (+)= dZ^T . H_chunk      (contraction over the chunk's tokens,
+//   reference     ref_k = h_k . W[ids_k]: the target logit, used only as the exponent shift;
+//   logits GEMM   Z^T tile = W_tile . H_chunk^T on bf16 MFMA with fp32 accumulators; the
+//                 epilogue never stores Z: it stores E = exp(z - ref_k) as bf16 in both
+//                 operand orientations (soft-max numerators: bf16 keeps their relative
+//                 precision), per (token, 128-row vocabulary granule) partial sums of E, and
+//                 the exact target logit;
+//   token stats   S_k = sum of the partials (fixed order), lse = ref + log S, log-prob, ratio,
+//                 clipped surrogate, c_k = dLoss/dlogp_k, beta_k = -c_k / S_k;
+//                 dz_kv = beta_k E_kv, except the target entry c_k (1 - p_target), which is
+//                 patched into E as -S_k (1 - p_target), computed in fp32 before rounding;
+//   dH GEMM       dH_chunk = diag(beta) (E . W)      (contraction over the vocabulary);
+//   dW GEMM       dW (+)= E^T . (diag(beta) H_chunk) (contraction over the chunk's tokens,
 //                 fp32, one owner per output tile, chunks in order: deterministic).
+// The shift by the target logit needs log(p_max / p_target) < 70 for every kept token (E is
+// clamped there); a token the current policy gives less than e^-70 of its mode's probability
+// does not occur for rollouts drawn from a behaviour policy inside the clip range.
 // All three contractions run through one "NT" kernel (both operands contiguous
 // along the contraction axis).  Every operand is kept in a blocked layout in the
 // workspace: blocks of 256 rows x 32 k-elements (16 KiB, contiguous), ordered k-fastest
@@ -54,17 +58,22 @@ __host__ __device__ __forceinline__ int64_t blk_off(int row, int k, int kb) {
 // in one or both orientations, zero-filling the padding:
 //   out_rk: rows = r (padded to Rp, multiple of 256), k = c (C must be a multiple of 32);
 //   out_cr: rows = c (padded to Cp, multiple of 256), k = r (padded to Rp).
+//   row_scale: optional [R] factor applied to row r of the input in out_cr (fp32 product, rounded once).
 __global__ void __launch_bounds__(256)
 pack_blocked_kernel(const uint16_t* __restrict__ in, int64_t ld_in, int R, int C, int Rp, int Cp,
-                    uint16_t* __restrict__ out_rk, uint16_t* __restrict__ out_cr) {
+                    uint16_t* __restrict__ out_rk, uint16_t* __restrict__ out_cr,
+                    const float* __restrict__ row_scale) {
   __shared__ uint16_t tile[64][66];
   const int r0 = blockIdx.x * 64, c0 = blockIdx.y * 64;
   const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
   for (int j = ty; j < 64; j += 4) {
     const int r = r0 + j, c = c0 + tx;
     const uint16_t x = (r < R && c < C) ? in[(int64_t)r * ld_in + c] : (uint16_t)0;
-    tile[j][tx] = x;
     if (out_rk && c < C) out_rk[blk_off(r, c, C >> 5)] = x;
+    if (row_scale && r < R)
+      tile[j][tx] = f32_to_bf16_bits(__builtin_bit_cast(float, (uint32_t)x << 16) * row_scale[r]);
+    else
+      tile[j][tx] = x;
   }
   if (!out_cr) return;
   __syncthreads();
@@ -237,7 +246,7 @@ gemm_nt_kernel(GemmArgs g, Epilogue epi) {
   __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));   // no direct-to-LDS load may outlive the block
   __syncthreads();
 
-  epi(acc, m0 + wm * 128, n0 + wn * 128, lane);
+  epi(acc, m0 + wm * 128, n0 + wn * 128, lane, wave, &lds[0][0][0]);
 }
 
 // ------------------------------------------------------------- epilogues ----
@@ -245,39 +254,28 @@ gemm_nt_kernel(GemmArgs g, Epilogue epi) {
 // Logits tile: rows = vocabulary (A = W), columns = tokens of the chunk (B = H_chunk).
 struct LogitsEpilogue {
   int V, n_valid;                  // vocabulary size, valid tokens in the chunk
-  int64_t ld_e;                    // leading dimension (tokens) of the partials
-  int kb_e;                        // k-slices (padded tokens / 32) of Et
-  uint16_t* Et;                    // blocked [Vp rows, padded tokens] bf16 out: exp(z - m_granule)
-  float* m_part; float* s_part;    // [Vp/128, ld_e]
-  float* z_target;                 // [ld_e]
+  int64_t ld_part;                 // leading dimension (tokens) of the partial sums
+  int kb_e, kb_z;                  // k-slices of Et (padded tokens / 32) and of Eb (Vp / 32)
+  uint16_t* Et;                    // blocked, rows = vocabulary, k = token: E = exp(z - ref)
+  uint16_t* Eb;                    // blocked, rows = token, k = vocabulary: the same values
+  float* s_part;                   // [Vp/128, ld_part] partial sums of E
+  float* z_target;                 // [ld_part] exact target logits
   const int32_t* ids;              // target ids of the chunk's tokens
+  const float* ref;                // [ld_part] exponent shift per token
 
-  __device__ __forceinline__ void operator()(f32x16 (&acc)[4][4], int v0, int k0, int lane) const {
+  static constexpr int kStageRow = 144;        // bytes per token row of the LDS staging tile (64 bf16 + pad)
+
+  __device__ __forceinline__ void operator()(f32x16 (&acc)[4][4], int v0, int k0, int lane, int wave, char* lds) const {
     const int l32 = lane & 31, lhi = lane >> 5;
     const int granule = v0 / kGranule;
     const bool all_rows_valid = v0 + kGranule <= V;
 #pragma unroll
     for (int nb = 0; nb < 4; ++nb) {
-      const int kk = k0 + nb * 32 + l32;                 // token column (always < ld_e)
-      const int y = kk < n_valid ? ids[kk] : -1;
-      float m = -INFINITY;
-      if (all_rows_valid) {
-#pragma unroll
-        for (int mb = 0; mb < 4; ++mb)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) m = fmaxf(m, acc[mb][nb][r]);
-      } else {
-#pragma unroll
-        for (int mb = 0; mb < 4; ++mb)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            const int v = v0 + mb * 32 + 8 * (r >> 2) + 4 * lhi + (r & 3);
-            if (v >= V) acc[mb][nb][r] = -INFINITY;
-            m = fmaxf(m, acc[mb][nb][r]);
-          }
-      }
-      m = fmaxf(m, __shfl_xor(m, 32));
-      // target logit, if the target row lies in this granule and in this lane's half
+      const int kk = k0 + nb * 32 + l32;                 // token column (always inside the padded chunk)
+      const bool tok_valid = kk < n_valid;
+      const int y = tok_valid ? ids[kk] : -1;
+      const float shift = tok_valid ? ref[kk] : 0.f;
+      // exact target logit, if the target row lies in this granule and in this lane's half
       const int yrel = y - v0;
       if (__any(yrel >= 0 && yrel < kGranule)) {
         if (yrel >= 0 && yrel < kGranule && ((yrel >> 2) & 1) == lhi) {
@@ -290,54 +288,101 @@ struct LogitsEpilogue {
           z_target[kk] = zt;
         }
       }
-      const float m_safe = m == -INFINITY ? 0.f : m;     // a granule entirely beyond V
       float s = 0.f;
 #pragma unroll
       for (int mb = 0; mb < 4; ++mb)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-          const float e = __expf(acc[mb][nb][r] - m_safe);
+          float e = __expf(fminf(acc[mb][nb][r] - shift, 70.f));
+          if (!all_rows_valid && v0 + mb * 32 + 8 * (r >> 2) + 4 * lhi + (r & 3) >= V) e = 0.f;
           s += e;
-          const int v = v0 + mb * 32 + 8 * (r >> 2) + 4 * lhi + (r & 3);
-          Et[blk_off(v, kk, kb_e)] = f32_to_bf16_bits(e);
+          acc[mb][nb][r] = e;
         }
       s += __shfl_xor(s, 32);
-      if (lhi == 0) {
-        m_part[(int64_t)granule * ld_e + kk] = m;
-        s_part[(int64_t)granule * ld_e + kk] = s;
+      if (lhi == 0) s_part[(int64_t)granule * ld_part + kk] = s;
+    }
+
+    // Et (rows = vocabulary, k = token): neighbouring lanes hold neighbouring tokens; an exchange
+    // with lane^1 lets even lanes store rows r (two tokens, 4 bytes) and odd lanes rows r+1.
+    const bool odd = lane & 1;
+#pragma unroll
+    for (int nb = 0; nb < 4; ++nb) {
+      const int kk_pair = k0 + nb * 32 + (l32 & ~1);
+#pragma unroll
+      for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+        for (int r = 0; r < 16; r += 2) {
+          const float x = acc[mb][nb][r], yv = acc[mb][nb][r + 1];
+          const float give = odd ? x : yv;
+          const float got = __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, give), 0xB1, 0xF, 0xF, true));
+          const float lo = odd ? got : x, hi = odd ? yv : got;
+          const uint32_t packed = (uint32_t)f32_to_bf16_bits(lo) | ((uint32_t)f32_to_bf16_bits(hi) << 16);
+          const int v = v0 + mb * 32 + 8 * (r >> 2) + 4 * lhi + (r & 3) + (odd ? 1 : 0);
+          *(uint32_t*)(Et + blk_off(v, kk_pair, kb_e)) = packed;
+        }
+    }
+
+    // Eb (rows = token, k = vocabulary): each lane holds 4 consecutive vocabulary entries of its
+    // token; stage 64 vocabulary rows at a time through LDS (free after the k-loop) so that the
+    // global stores are 16 bytes per lane and contiguous (128 tokens x 64 bytes per k-slice).
+    char* stage = lds + wave * (128 * kStageRow);
+#pragma unroll
+    for (int half = 0; half < 2; ++half) {
+      __syncthreads();
+#pragma unroll
+      for (int nb = 0; nb < 4; ++nb)
+#pragma unroll
+        for (int mbh = 0; mbh < 2; ++mbh)
+#pragma unroll
+          for (int r4 = 0; r4 < 4; ++r4) {
+            const f32x16& a = acc[half * 2 + mbh][nb];
+            uint2 w;
+            w.x = (uint32_t)f32_to_bf16_bits(a[4 * r4]) | ((uint32_t)f32_to_bf16_bits(a[4 * r4 + 1]) << 16);
+            w.y = (uint32_t)f32_to_bf16_bits(a[4 * r4 + 2]) | ((uint32_t)f32_to_bf16_bits(a[4 * r4 + 3]) << 16);
+            *(uint2*)(stage + (nb * 32 + l32) * kStageRow + (mbh * 32 + 8 * r4 + 4 * lhi) * 2) = w;
+          }
+      __syncthreads();
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const int q = i * 64 + lane;                    // slice q/512, token (q%512)/4, 16-byte chunk q%4
+        const int sl = q >> 9, tok = (q & 511) >> 2, ch = q & 3;
+        const uint4 val = *(const uint4*)(stage + tok * kStageRow + sl * 64 + ch * 16);
+        *(uint4*)(Eb + blk_off(k0 + tok, v0 + half * 64 + sl * 32 + ch * 8, kb_z)) = val;
       }
     }
   }
 };
 
-// dH tile: rows = tokens of the chunk (A = dZ), columns = hidden units (B = W^T).
+// dH tile: rows = tokens of the chunk (A = E), columns = hidden units (B = W^T); rows scaled by beta.
 struct DHiddenEpilogue {
   int n_valid, H;
   uint16_t* dH;                    // rows of this chunk, [n_valid, H] bf16
+  const float* beta;               // [n_valid]
 
-  __device__ __forceinline__ void operator()(f32x16 (&acc)[4][4], int k0, int h0, int lane) const {
+  __device__ __forceinline__ void operator()(f32x16 (&acc)[4][4], int k0, int h0, int lane, int, char*) const {
     const int l32 = lane & 31, lhi = lane >> 5;
 #pragma unroll
-    for (int nb = 0; nb < 4; ++nb) {
-      const int h = h0 + nb * 32 + l32;
-      if (h >= H) continue;
+    for (int mb = 0; mb < 4; ++mb)
 #pragma unroll
-      for (int mb = 0; mb < 4; ++mb)
+      for (int r = 0; r < 16; ++r) {
+        const int k = k0 + mb * 32 + 8 * (r >> 2) + 4 * lhi + (r & 3);
+        if (k >= n_valid) continue;
+        const float b = beta[k];
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int k = k0 + mb * 32 + 8 * (r >> 2) + 4 * lhi + (r & 3);
-          if (k < n_valid) dH[(int64_t)k * H + h] = f32_to_bf16_bits(acc[mb][nb][r]);
+        for (int nb = 0; nb < 4; ++nb) {
+          const int h = h0 + nb * 32 + l32;
+          if (h < H) dH[(int64_t)k * H + h] = f32_to_bf16_bits(b * acc[mb][nb][r]);
         }
-    }
+      }
   }
 };
 
-// dW tile: rows = vocabulary (A = dZ^T), columns = hidden units (B = H_chunk^T).
+// dW tile: rows = vocabulary (A = E^T), columns = hidden units (B = (diag(beta) H_chunk)^T).
 struct DWeightEpilogue {
   int V, H, accumulate;
   float* dW;                       // [V, H] fp32
 
-  __device__ __forceinline__ void operator()(f32x16 (&acc)[4][4], int v0, int h0, int lane) const {
+  __device__ __forceinline__ void operator()(f32x16 (&acc)[4][4], int v0, int h0, int lane, int, char*) const {
     const int l32 = lane & 31, lhi = lane >> 5;
 #pragma unroll
     for (int nb = 0; nb < 4; ++nb) {
@@ -357,121 +402,73 @@ struct DWeightEpilogue {
   }
 };
 
-// ------------------------------------------------- per-token statistics ----
-// 64 tokens per workgroup; the granules of a token are split over 4 wavefronts (granule
-// gi goes to wavefront gi % 4), each keeping a running (max, sum); the four partial pairs
-// are merged in wavefront order, so the result does not depend on timing.
+// ----------------------------------------------------- reference logit ----
+// ref[kk] = h_k . W[ids_k] in fp32, one wavefront per token (row-major caller arrays).
 __global__ void __launch_bounds__(256)
-token_stats_kernel(const float* __restrict__ m_part, const float* __restrict__ s_part, int n_granules, int64_t ld,
+target_logit_kernel(const uint16_t* __restrict__ hidden, const uint16_t* __restrict__ W, const int32_t* __restrict__ ids,
+                    int n_valid, int H, float* __restrict__ ref) {
+  const int kk = blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int lane = threadIdx.x & 63;
+  if (kk >= n_valid) return;
+  const uint4* hp = (const uint4*)(hidden + (int64_t)kk * H);
+  const uint4* wp = (const uint4*)(W + (int64_t)ids[kk] * H);
+  float s = 0.f;
+  for (int j = lane; j < H / 8; j += 64) {
+    const uint4 a = hp[j], b = wp[j];
+    const uint32_t aw[4] = {a.x, a.y, a.z, a.w}, bw[4] = {b.x, b.y, b.z, b.w};
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      s = fmaf(__builtin_bit_cast(float, aw[q] << 16), __builtin_bit_cast(float, bw[q] << 16), s);
+      s = fmaf(__builtin_bit_cast(float, aw[q] & 0xffff0000u), __builtin_bit_cast(float, bw[q] & 0xffff0000u), s);
+    }
+  }
+  for (int off = 32; off > 0; off >>= 1) s += __shfl_xor(s, off);
+  if (lane == 0) ref[kk] = s;
+}
+
+// ------------------------------------------------- per-token statistics ----
+// 64 tokens per workgroup; the granules of a token are split over 4 wavefronts (granule gi goes
+// to wavefront gi % 4) and the four partial sums are added in wavefront order, so the result
+// does not depend on timing.
+__global__ void __launch_bounds__(256)
+token_stats_kernel(const float* __restrict__ s_part, int n_granules, int64_t ld, const float* __restrict__ ref,
                    const float* __restrict__ z_target, int n_valid, int chunk_start,
                    const float* __restrict__ old_logp, const float* __restrict__ adv,
                    const int32_t* __restrict__ kept_seq, const float* __restrict__ kept_w,
                    float eps_lo, float eps_hi, float grad_scale,
-                   float* __restrict__ lse_out, float* __restrict__ c_out, float* __restrict__ logp_chunk,
+                   float* __restrict__ beta_out, float* __restrict__ patch_out,
                    float* __restrict__ logp_out, float* __restrict__ term) {
-  __shared__ float m_s[4][64], s_s[4][64];
+  __shared__ float s_s[4][64];
   const int t = threadIdx.x & 63, part = threadIdx.x >> 6;
   const int kk = blockIdx.x * 64 + t;
-  float m = -INFINITY, s = 0.f;
-  if (kk < n_valid) {
-    for (int gi = part; gi < n_granules; gi += 4) {
-      const float mg = m_part[(int64_t)gi * ld + kk];
-      const float sg = s_part[(int64_t)gi * ld + kk];
-      if (mg == -INFINITY) continue;                    // granule entirely beyond the vocabulary
-      if (mg > m) { s = s * __expf(m - mg) + sg; m = mg; }
-      else s += sg * __expf(mg - m);
-    }
-  }
-  m_s[part][t] = m;
+  float s = 0.f;
+  if (kk < n_valid)
+    for (int gi = part; gi < n_granules; gi += 4) s += s_part[(int64_t)gi * ld + kk];
   s_s[part][t] = s;
   __syncthreads();
   if (part != 0 || kk >= n_valid) return;
-  m = fmaxf(fmaxf(m_s[0][t], m_s[1][t]), fmaxf(m_s[2][t], m_s[3][t]));
-  s = 0.f;
-#pragma unroll
-  for (int q = 0; q < 4; ++q)
-    if (m_s[q][t] != -INFINITY) s += s_s[q][t] * __expf(m_s[q][t] - m);
-  const float lse = m + logf(s);
+  const float S = (s_s[0][t] + s_s[1][t]) + (s_s[2][t] + s_s[3][t]);
+  const float lse = ref[kk] + logf(S);
   const float logp = z_target[kk] - lse;
   const int k = chunk_start + kk;
   const float w = kept_w[k];
   const TokenScalars ts = grpo_token_scalars(logp, old_logp[k], adv[kept_seq[k]], w, eps_lo, eps_hi, grad_scale);
-  lse_out[kk] = lse;
-  c_out[kk] = ts.c;
-  logp_chunk[kk] = logp;
+  beta_out[kk] = -ts.c / S;                            // dz_kv = beta_k E_kv off the target
+  patch_out[kk] = -S * (1.f - __expf(logp));           // E'_target with beta_k E' = c_k (1 - p_target)
   if (logp_out) logp_out[k] = logp;
   term[k] = w * ts.S;
 }
 
-// ------------------------------------------------------------- rescale ----
-// One block of Et (256 vocabulary rows x 32 tokens, 16 KiB contiguous) per workgroup.
-// In place: dZ^T = -c_k exp(m_granule - lse_k) E, with the target entry replaced by
-// c_k (1 - softmax_target) computed in fp32.  The same values are written transposed into
-// dZ (rows = tokens, k = vocabulary), also blocked.
+// Overwrite the target entry of every valid token in both copies of E (see token_stats_kernel).
 __global__ void __launch_bounds__(256)
-rescale_kernel(uint16_t* __restrict__ Et, int kb_e, uint16_t* __restrict__ dZ, int kb_z,
-               const float* __restrict__ m_part, int64_t ld_part, const float* __restrict__ lse,
-               const float* __restrict__ c, const float* __restrict__ logp_chunk,
-               const int32_t* __restrict__ ids, int n_valid) {
-  __shared__ __attribute__((aligned(16))) uint16_t tr[32][256 + 8];   // [token][vocab row], padded rows
-  __shared__ float alpha_s[2][32];
-  __shared__ float onehot_s[32];
-  __shared__ int y_s[32];
-  const int vt = blockIdx.x, ks = blockIdx.y;          // vocabulary tile (256 rows), token slice (32)
-  const int tid = threadIdx.x;
-  if (tid < 64) {
-    const int t = tid & 31, gsel = tid >> 5;
-    const int kk = ks * 32 + t;
-    float alpha = 0.f;
-    if (kk < n_valid) {
-      const float mg = m_part[(int64_t)(vt * 2 + gsel) * ld_part + kk];
-      const float ck = c[kk];
-      alpha = mg == -INFINITY ? 0.f : -ck * __expf(mg - lse[kk]);
-      if (gsel == 0) {
-        onehot_s[t] = ck * (1.f - __expf(logp_chunk[kk]));
-        y_s[t] = ids[kk];
-      }
-    } else if (gsel == 0) {
-      onehot_s[t] = 0.f;
-      y_s[t] = -1;
-    }
-    alpha_s[gsel][t] = alpha;
-  }
-  __syncthreads();
-  uint4* blk = (uint4*)(Et + ((int64_t)vt * kb_e + ks) * kBlkElems);
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int q = i * 256 + tid;                       // 16-byte chunk: row q/4, tokens (q%4)*8 .. +7
-    const int vr = q >> 2, t0 = (q & 3) << 3;
-    const int v = vt * 256 + vr;
-    const uint4 in = blk[q];
-    const uint32_t w[4] = {in.x, in.y, in.z, in.w};
-    uint32_t o[4];
-#pragma unroll
-    for (int h = 0; h < 4; ++h) {
-      uint32_t packed = 0;
-#pragma unroll
-      for (int half = 0; half < 2; ++half) {
-        const int t = t0 + 2 * h + half;
-        const float e = __builtin_bit_cast(float, (half ? (w[h] & 0xffff0000u) : (w[h] << 16)));
-        const float dz = (v == y_s[t]) ? onehot_s[t] : alpha_s[vr >> 7][t] * e;
-        const uint16_t bits = f32_to_bf16_bits(dz);
-        tr[t][vr] = bits;
-        packed |= (uint32_t)bits << (16 * half);
-      }
-      o[h] = packed;
-    }
-    blk[q] = make_uint4(o[0], o[1], o[2], o[3]);
-  }
-  __syncthreads();
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int q = i * 256 + tid;                       // token q/32, vocabulary rows (q%32)*8 .. +7
-    const int t = q >> 5, vr0 = (q & 31) << 3;
-    const int kk = ks * 32 + t;
-    const uint4 val = *(const uint4*)&tr[t][vr0];
-    *(uint4*)(dZ + blk_off(kk, vt * 256 + vr0, kb_z)) = val;
-  }
+patch_target_kernel(uint16_t* __restrict__ Et, int kb_e, uint16_t* __restrict__ Eb, int kb_z,
+                    const int32_t* __restrict__ ids, const float* __restrict__ patch, int n_valid) {
+  const int kk = blockIdx.x * blockDim.x + threadIdx.x;
+  if (kk >= n_valid) return;
+  const int y = ids[kk];
+  const uint16_t bits = f32_to_bf16_bits(patch[kk]);
+  Et[blk_off(y, kk, kb_e)] = bits;
+  Eb[blk_off(kk, y, kb_z)] = bits;
 }
 
 // -------------------------------------------------------------- host side ----
@@ -479,8 +476,7 @@ static inline int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * 
 
 struct Bf16Plan {
   int64_t Vp, Hp; int n_granules; int cap;      // padded vocabulary / hidden size, granules, chunk capacity (tokens)
-  size_t off_Wb, off_Wtb, off_Hb, off_Hktb, off_Et, off_dZ, off_m, off_s, off_zt, off_lse, off_c, off_logp,
-      off_term, total;
+  size_t off_Wb, off_Wtb, off_Hb, off_Hktb, off_Et, off_Eb, off_s, off_zt, off_ref, off_beta, off_patch, off_term, total;
 };
 
 static Bf16Plan make_plan(int32_t N_k, int32_t H, int32_t V, int cap) {
@@ -495,14 +491,13 @@ static Bf16Plan make_plan(int32_t N_k, int32_t H, int32_t V, int cap) {
   p.off_Wtb = take((size_t)p.Hp * p.Vp * 2);    // W^T:  rows = hidden,     k = vocabulary
   p.off_Hb = take((size_t)cap * H * 2);         // H_chunk:   rows = tokens, k = hidden
   p.off_Hktb = take((size_t)p.Hp * cap * 2);    // H_chunk^T: rows = hidden, k = tokens
-  p.off_Et = take((size_t)p.Vp * cap * 2);      // E then dZ^T: rows = vocabulary, k = tokens
-  p.off_dZ = take((size_t)cap * p.Vp * 2);      // dZ:   rows = tokens, k = vocabulary
-  p.off_m = take((size_t)p.n_granules * cap * 4);
+  p.off_Et = take((size_t)p.Vp * cap * 2);      // E: rows = vocabulary, k = tokens
+  p.off_Eb = take((size_t)cap * p.Vp * 2);      // E: rows = tokens, k = vocabulary
   p.off_s = take((size_t)p.n_granules * cap * 4);
   p.off_zt = take((size_t)cap * 4);
-  p.off_lse = take((size_t)cap * 4);
-  p.off_c = take((size_t)cap * 4);
-  p.off_logp = take((size_t)cap * 4);
+  p.off_ref = take((size_t)cap * 4);
+  p.off_beta = take((size_t)cap * 4);
+  p.off_patch = take((size_t)cap * 4);
   p.off_term = take((size_t)(N_k > 0 ? N_k : 1) * 4);
   p.total = off;
   return p;
@@ -538,13 +533,12 @@ nat_status loss_bf16_run(const LossArgs& a) {
   uint16_t* Hb = (uint16_t*)(ws + p.off_Hb);
   uint16_t* Hktb = (uint16_t*)(ws + p.off_Hktb);
   uint16_t* Et = (uint16_t*)(ws + p.off_Et);
-  uint16_t* dZ = (uint16_t*)(ws + p.off_dZ);
-  float* m_part = (float*)(ws + p.off_m);
+  uint16_t* Eb = (uint16_t*)(ws + p.off_Eb);
   float* s_part = (float*)(ws + p.off_s);
   float* zt = (float*)(ws + p.off_zt);
-  float* lse = (float*)(ws + p.off_lse);
-  float* c = (float*)(ws + p.off_c);
-  float* logp_chunk = (float*)(ws + p.off_logp);
+  float* ref = (float*)(ws + p.off_ref);
+  float* beta = (float*)(ws + p.off_beta);
+  float* patch = (float*)(ws + p.off_patch);
   float* term = (float*)(ws + p.off_term);
   const uint16_t* W = (const uint16_t*)a.W;
   const uint16_t* hidden = (const uint16_t*)a.hidden;
@@ -553,39 +547,43 @@ nat_status loss_bf16_run(const LossArgs& a) {
 
   {  // W and W^T in the blocked layout, padding zero-filled
     ProfScope prof(PC_TRANSPOSE, s);
-    pack_blocked_kernel<<<dim3(Vp / 64, Hp / 64), 256, 0, s>>>(W, H, V, H, Vp, Hp, Wb, Wtb);
+    pack_blocked_kernel<<<dim3(Vp / 64, Hp / 64), 256, 0, s>>>(W, H, V, H, Vp, Hp, Wb, Wtb, nullptr);
     NAT_LAUNCH_CHECK();
   }
   for (int c0 = 0; c0 < a.N_k; c0 += cap) {
     const int nv = a.N_k - c0 < cap ? a.N_k - c0 : cap;
     const int np = (int)round_up(nv, kBN);
-    {  // H_chunk and H_chunk^T in the blocked layout
+    const uint16_t* hid_c = hidden + (int64_t)c0 * H;
+    {  // H_chunk in the blocked layout; exponent shift = target logit
       ProfScope prof(PC_TRANSPOSE, s);
-      pack_blocked_kernel<<<dim3(np / 64, Hp / 64), 256, 0, s>>>(hidden + (int64_t)c0 * H, H, nv, H, np, Hp, Hb, Hktb);
+      pack_blocked_kernel<<<dim3(np / 64, H / 64), 256, 0, s>>>(hid_c, H, nv, H, np, Hp, Hb, nullptr, nullptr);
+      NAT_LAUNCH_CHECK();
+      target_logit_kernel<<<(nv + 3) / 4, 256, 0, s>>>(hid_c, W, a.ids + c0, nv, H, ref);
       NAT_LAUNCH_CHECK();
     }
     {  // logits: rows = vocabulary, columns = tokens, contraction over the hidden size
       GemmArgs g{Wb, Hb, H, Vp / kBM, np / kBN};
-      LogitsEpilogue e{V, nv, cap, np / 32, Et, m_part, s_part, zt, a.ids + c0};
+      LogitsEpilogue e{V, nv, cap, np / 32, Vp / 32, Et, Eb, s_part, zt, a.ids + c0, ref};
       nat_status st = launch_gemm(g, e, PC_LOGITS, s);
       if (st != NAT_OK) return st;
     }
     {
       ProfScope prof(PC_TOKEN_STATS, s);
-      token_stats_kernel<<<(nv + 63) / 64, 256, 0, s>>>(m_part, s_part, p.n_granules, cap, zt, nv, c0, a.old_logp,
-                                                         a.adv, a.kept_seq, a.kept_w, a.eps_lo, a.eps_hi,
-                                                         a.grad_scale, lse, c, logp_chunk, a.logp, term);
+      token_stats_kernel<<<(nv + 63) / 64, 256, 0, s>>>(s_part, p.n_granules, cap, ref, zt, nv, c0, a.old_logp, a.adv,
+                                                       a.kept_seq, a.kept_w, a.eps_lo, a.eps_hi, a.grad_scale,
+                                                       beta, patch, a.logp, term);
+      NAT_LAUNCH_CHECK();
+      patch_target_kernel<<<(nv + 255) / 256, 256, 0, s>>>(Et, np / 32, Eb, Vp / 32, a.ids + c0, patch, nv);
       NAT_LAUNCH_CHECK();
     }
-    {
-      ProfScope prof(PC_RESCALE, s);
-      rescale_kernel<<<dim3(Vp / 256, np / 32), 256, 0, s>>>(Et, np / 32, dZ, Vp / 32, m_part, cap, lse, c,
-                                                            logp_chunk, a.ids + c0, nv);
+    {  // (diag(beta) H_chunk)^T in the blocked layout
+      ProfScope prof(PC_TRANSPOSE, s);
+      pack_blocked_kernel<<<dim3(np / 64, Hp / 64), 256, 0, s>>>(hid_c, H, nv, H, np, Hp, nullptr, Hktb, beta);
       NAT_LAUNCH_CHECK();
     }
     {  // dH: rows = tokens, columns = hidden units, contraction over the padded vocabulary
-      GemmArgs g{dZ, Wtb, Vp, np / kBM, Hp / kBN};
-      DHiddenEpilogue e{nv, H, (uint16_t*)a.dH + (int64_t)c0 * H};
+      GemmArgs g{Eb, Wtb, Vp, np / kBM, Hp / kBN};
+      DHiddenEpilogue e{nv, H, (uint16_t*)a.dH + (int64_t)c0 * H, beta};
       nat_status st = launch_gemm(g, e, PC_DHIDDEN, s);
       if (st != NAT_OK) return st;
     }

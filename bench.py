@@ -27,12 +27,16 @@ def parse_args():
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--workload", default="qwen3_8b_head_rpc")
-    ap.add_argument("--scheme", default=None, help="rpc | urs | full | det (default: the workload's own)")
+    ap.add_argument("--scheme", default=None,
+                    help="rpc | urs | full | det | mixed (even prompts URS, odd prompts Det.Trunc. 50%%); "
+                         "default: the workload's own")
     ap.add_argument("--p", type=float, default=0.5)
     ap.add_argument("--min-cut", type=int, default=1)
     ap.add_argument("--seed", type=int, default=2000)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--prompts", type=int, default=None, help="override the number of prompts (smaller batch)")
+    ap.add_argument("--stress-select", type=int, default=0, metavar="LOG2_TOKENS",
+                    help="instead of the loss benchmark: time nat_select / nat_compact alone on 2^LOG2_TOKENS tokens")
     return ap.parse_args()
 
 
@@ -61,8 +65,11 @@ def cpu_baseline(batch, old_logp, scheme_code, args, torch):
     R = batch["rewards"]
     t0 = time.perf_counter()
     adv = ogrpo.advantages(R).reshape(-1)[:len(lens)]
-    d = osel.select(cu, scheme_code, p=args.p, C=args.min_cut, beta=0.5, seed=args.seed, step=0)
-    c = osel.compact(d["mask"], cu, len(lens), scheme_code, p=args.p, C=args.min_cut)
+    spr = None
+    if args.scheme_name == "mixed":
+        spr = np.array([osel.URS if (i // batch["G"]) % 2 == 0 else osel.DET for i in range(len(lens))])
+    d = osel.select(cu, scheme_code, p=args.p, C=args.min_cut, beta=0.5, seed=args.seed, step=0, scheme_per_rollout=spr)
+    c = osel.compact(d["mask"], cu, len(lens), scheme_code, p=args.p, C=args.min_cut, scheme_per_rollout=spr)
     k = c["kept_idx"]
     out = ogrpo.loss_and_grads(hidden[k], W, ids[k], old[k], adv[c["kept_seq"]], c["kept_w"].astype(np.float64))
     dt = time.perf_counter() - t0
@@ -73,8 +80,63 @@ def cpu_baseline(batch, old_logp, scheme_code, args, torch):
                 loss=out["loss"])
 
 
+def stress_select(args):
+    """HBM-side measurement of the selection kernels on an inflated batch (they are launch-latency
+    bound at the real workloads): algorithmic bytes = N/8 mask bytes written by nat_select;
+    N/8 read + 12 bytes written per kept token by nat_compact."""
+    import numpy as np
+    import torch
+    import paper_2603_06619_amd as nat
+    dev = "cuda:0"
+    N = 1 << args.stress_select
+    B = 4096
+    rng = np.random.default_rng(1)
+    cuts = np.sort(rng.choice(np.arange(1, N), size=B - 1, replace=False))
+    cu = torch.from_numpy(np.concatenate([[0], cuts, [N]]).astype(np.int64)).to(dev)
+    out = {}
+    cut_len = torch.empty(B, dtype=torch.int32, device=dev)
+    mask = torch.empty(nat.mask_words(N), dtype=torch.int32, device=dev)
+    kept_idx = torch.empty(N, dtype=torch.int32, device=dev)
+    kept_seq = torch.empty(N, dtype=torch.int32, device=dev)
+    kept_w = torch.empty(N, dtype=torch.float32, device=dev)
+    cu_kept = torch.empty(B + 1, dtype=torch.int32, device=dev)
+    n_kept = torch.empty(1, dtype=torch.int32, device=dev)
+    ws = torch.empty(nat.compact_workspace_bytes(N), dtype=torch.uint8, device=dev)
+    src = torch.empty(N, dtype=torch.int32, device=dev)
+    dst = torch.empty_like(src)
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+
+    def timed(fn, reps=5):
+        fn()
+        torch.cuda.synchronize()
+        best = 1e9
+        for _ in range(reps):
+            a, b = ev(), ev()
+            a.record(); fn(); b.record(); torch.cuda.synchronize()
+            best = min(best, a.elapsed_time(b))
+        return best
+
+    copy_ms = timed(lambda: dst.copy_(src))
+    out["copy_GBps"] = 2 * 4 * N / copy_ms / 1e6
+    for name, code, kw in (("urs", nat.URS, dict(p=0.5)), ("rpc", nat.RPC, dict(min_cut=1))):
+        params = nat.SelectParams(code, seed=3, **kw)
+        sel_ms = timed(lambda: nat.nat_select(params, cu, B, N, cut_len, mask))
+        cmp_ms = timed(lambda: nat.nat_compact(params, B, mask, cu, B, N, kept_idx, kept_seq, kept_w, cu_kept, n_kept,
+                                               None, ws))
+        nk = int(n_kept.item())
+        out[name] = dict(tokens=N, kept=nk, select_ms=sel_ms, compact_ms=cmp_ms,
+                         select_GBps=(N / 8) / sel_ms / 1e6, compact_GBps=(N / 8 + 12.0 * nk) / cmp_ms / 1e6,
+                         select_Gtok_per_s=N / sel_ms / 1e6, compact_Gtok_per_s=N / cmp_ms / 1e6)
+    print(json.dumps({"metric": "nat_select / nat_compact on an inflated batch", "n_gpus": 1, "data": "synthetic",
+                      "config": {"workload": f"2^{args.stress_select} tokens in {B} rollouts"}, **out}))
+
+
 def main():
     args = parse_args()
+    if args.stress_select:
+        if args.gpus != 1:
+            sys.exit(2)
+        return stress_select(args)
     if args.gpus != 1:
         print(f"bench.py measures one GPU only (got --gpus {args.gpus}); the path shards by rollout, "
               "see DESIGN.md", file=sys.stderr)
@@ -94,16 +156,21 @@ def main():
     stage = LossStage(dev)
 
     default_scheme = {"qwen3_8b_head_rpc": "rpc", "qwen3_0p6b_head": "urs", "qwen3_8b_long_cot": "urs",
-                      "wide_head_stress": "urs", "tiny_fp32": "urs"}[args.workload]
+                      "wide_head_stress": "mixed", "tiny_fp32": "urs"}[args.workload]
     scheme_name = args.scheme or default_scheme
-    scheme_code = dict(full=nat.FULL, urs=nat.URS, rpc=nat.RPC, det=nat.DET)[scheme_name]
+    scheme_code = dict(full=nat.FULL, urs=nat.URS, rpc=nat.RPC, det=nat.DET, mixed=nat.URS)[scheme_name]
 
+    args.scheme_name = scheme_name
     batch = si.make_batch_torch(args.workload, args.seed, dev, P=args.prompts)
     P, G, B, N, H, V = batch["P"], batch["G"], batch["B"], batch["N"], batch["H"], batch["V"]
     old_logp = si.behaviour_logp_stand_in(batch["hidden"], batch["W"], batch["ids"], batch["logp_noise"])
     rewards = torch.from_numpy(batch["rewards"].reshape(-1)).to(dev)
     cu = torch.from_numpy(batch["cu_seqlens"]).to(dev)
-    params = nat.SelectParams(scheme_code, p=args.p, min_cut=args.min_cut, trunc_frac=0.5, seed=args.seed, step=0)
+    spr = None
+    if scheme_name == "mixed":
+        spr = torch.tensor([nat.URS if (i // G) % 2 == 0 else nat.DET for i in range(B)], dtype=torch.int32, device=dev)
+    params = nat.SelectParams(scheme_code, p=args.p, min_cut=args.min_cut, trunc_frac=0.5, seed=args.seed, step=0,
+                              scheme_per_rollout=spr)
     dW = torch.empty((V, H), dtype=torch.float32, device=dev)
     dtype_code = nat.DTYPE_BF16 if batch["dtype"] == "bf16" else nat.DTYPE_F32
 
@@ -170,6 +237,7 @@ def main():
                                             if gemm_ms > 0 else None),
         "gpu_event_ms_per_step": ms_total / args.steps,
         "loss": float(out["loss"].item()),
+        "peak_hbm_gb": torch.cuda.max_memory_allocated() / 1e9,
         "roofline": roofline,
         "kernels": kernels,
     }

@@ -13,8 +13,8 @@ constexpr int kTileTokens = 4096;                 // tokens per scatter block
 constexpr int kTileWords = kTileTokens / 32;      // 128 mask words
 constexpr int kScatterThreads = 256;              // 4 wavefronts x 1024 tokens
 
-__device__ __forceinline__ int rollout_of_pos(const int64_t* __restrict__ cu, int B, int64_t n) {
-  int lo = 0, hi = B;
+// last i in [lo, hi) with cu[i] <= n; the caller guarantees cu[lo] <= n < cu[hi]
+__device__ __forceinline__ int rollout_of_pos(const int64_t* __restrict__ cu, int lo, int hi, int64_t n) {
   while (hi - lo > 1) {
     const int mid = (lo + hi) >> 1;
     if (cu[mid] <= n) lo = mid; else hi = mid;
@@ -102,6 +102,15 @@ compact_scatter_kernel(SelectArgs a, double n_rollouts, const uint32_t* __restri
   __syncthreads();
   int base = tile_offset[blockIdx.x];
   for (int w = 0; w < wave; ++w) base += wave_cnt[w];
+  // rollouts touched by this wavefront's 1024 tokens: two wave-uniform searches bound the per-lane ones
+  const int64_t N = cu[B];
+  const int64_t span_first = word0 * 32;
+  int i_lo = 0, i_hi = B;
+  if (span_first < N) {
+    const int64_t span_last = span_first + 1023 < N ? span_first + 1023 : N - 1;
+    i_lo = rollout_of_pos(cu, 0, B, span_first);
+    i_hi = rollout_of_pos(cu, i_lo, B, span_last) + 1;
+  }
 
   for (int it = 0; it < 16; ++it) {
     const uint32_t lo = __shfl(my_word, 2 * it), hi = __shfl(my_word, 2 * it + 1);
@@ -111,7 +120,7 @@ compact_scatter_kernel(SelectArgs a, double n_rollouts, const uint32_t* __restri
     const int rank = __popcll(group & ((1ull << lane) - 1ull));
     if (keep) {
       const int64_t n = (word0 + 2 * it) * 32 + lane;
-      const int i = rollout_of_pos(cu, B, n);
+      const int i = rollout_of_pos(cu, i_lo, i_hi, n);
       const int64_t start = cu[i];
       const int64_t T = cu[i + 1] - start;
       const int scheme = a.scheme_per_rollout ? a.scheme_per_rollout[i] : a.scheme;

@@ -159,8 +159,10 @@ size_t nat_loss_workspace_min_bytes(int32_t N_k, int32_t H, int32_t V, int32_t d
  *   d_dH_k [N_k, H] out, same dtype as the inputs;
  *   d_dW [V, H] float32 out: overwritten, or added to when accumulate_dw != 0.
  *   The reduction order of d_dW and d_loss is fixed: results are bit-identical from run to run.
- *   The [N_k, V] logits are never written to memory as a whole; the bf16 path keeps a
- *   bounded bf16 tile of soft-max numerators for one token chunk in the workspace.
+ *   The [N_k, V] logits are never written to memory as a whole; the bf16 path keeps the bf16
+ *   soft-max numerators exp(z - z_target) of one token chunk (at most 32768 tokens) in the
+ *   workspace.  That shift requires log(p_max / p_target) < 70 for every kept token (larger
+ *   numerators are clamped); the fp32 path has no such bound.
  * N_k = 0 is valid: loss = 0, d_dW zeroed unless accumulating, d_dH_k untouched.
  * Errors: NULL pointer, N_k < 0, eps < 0 -> NAT_INVALID_ARG; H <= 0, V <= 0, or (bf16) H not
  * a multiple of 64 -> NAT_BAD_SHAPE; dtype unknown -> NAT_UNSUPPORTED_DTYPE; ws_bytes below

@@ -75,6 +75,26 @@ def test_bf16_grad_scale_and_eps(stage):
     assert ((ref["r"] > 1.28) | (ref["r"] < 0.9)).sum() > 10
 
 
+def test_bf16_peaked_softmax_and_unlikely_targets(stage):
+    # logits with a spread of ~ +-20: half the targets are the arg-max (p close to 1, the one-hot
+    # term nearly cancels), the rest are random (log(p_max / p_target) up to ~ 40, inside the bound of 70)
+    import synth_inputs as si
+    from oracle import grpo as ogrpo
+    n_tok, H, V = 400, 128, 2000
+    case = make_loss_case(31, n_tok, H, V, "bf16", noise=0.1, w_std=0.5)
+    Z = case["hidden"].astype(np.float64) @ case["W"].astype(np.float64).T
+    ids = case["ids"].copy()
+    ids[::2] = Z[::2].argmax(axis=1)
+    case["ids"] = ids.astype(np.int32)
+    logp = ogrpo.token_logp(case["hidden"], case["W"], case["ids"])
+    case["old_logp"] = (logp + np.random.default_rng(5).standard_normal(n_tok) * 0.1).astype(np.float32)
+    gap = Z.max(axis=1) - Z[np.arange(n_tok), ids]
+    assert gap.max() > 20 and gap.max() < 65 and (np.exp(logp[::2]) > 0.5).sum() > 50
+    ref = oracle_loss(**case)
+    out = hip_loss(stage, case, "bf16")
+    check(out, ref, n_tok, TOL_BF16)
+
+
 def test_bf16_multiple_chunks_and_accumulate(stage):
     import paper_2603_06619_amd as nat
     n_tok, H, V = 600, 128, 3000

@@ -216,6 +216,12 @@ gemm_nt_kernel(GemmArgs g, Epilogue epi) {
       __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);     // 1 LDS read
     }
     __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
+    // keep all 16 MFMAs of the first substep on this side of the barrier (their fragment
+    // registers are overwritten right after it)
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) asm volatile("" : "+a"(acc[i][j]));
     __builtin_amdgcn_sched_barrier(0);
     // slice kt+1 has landed (this wavefront's share; the barrier covers the others) and this
     // wavefront has finished reading slice kt, whose buffer is refilled below

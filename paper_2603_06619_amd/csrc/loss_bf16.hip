@@ -49,9 +49,13 @@ __device__ __forceinline__ uint16_t f32_to_bf16_bits(float x) {
 // ------------------------------------------------------------ blocked layout ----
 constexpr int kBlkElems = 256 * 32;               // one block: 256 rows x 32 k-elements
 
-// element (row, k) of an operand with kb = K/32 k-slices
+// element (row, k) of an operand with kb = K/32 k-slices.  Inside a row of a block the four
+// 16-byte chunks are stored permuted (chunk index XOR bits 2..3 of the row): a block is then a
+// byte-for-byte image of the bank-conflict-free LDS tile, and the direct-to-LDS copy reads it
+// linearly, 16 bytes per lane.
 __host__ __device__ __forceinline__ int64_t blk_off(int row, int k, int kb) {
-  return ((int64_t)(row >> 8) * kb + (k >> 5)) * kBlkElems + ((row & 255) << 5) + (k & 31);
+  return ((int64_t)(row >> 8) * kb + (k >> 5)) * kBlkElems + ((row & 255) << 5) +
+         (((((k & 31) >> 3) ^ ((row >> 2) & 3))) << 3) + (k & 7);
 }
 
 // Repack a row-major matrix in [R, C] (leading dimension ld_in) into the blocked layout,
@@ -117,16 +121,14 @@ __device__ __forceinline__ int lds_chunk_off(int r, int c) { return r * (kBK * 2
 
 // Global -> LDS copy of one [256][32] bf16 operand block (16 KiB, contiguous in memory)
 // without staging registers: each wavefront issues 4 direct-to-LDS loads of 16 bytes per
-// lane.  One instruction fills 16 consecutive tile rows (1 KiB); the hardware places lane l
-// at byte 16*l of that KiB, so the LDS swizzle is applied by choosing which 16-byte chunk of
-// its row a lane fetches: lane l -> row l/4, logical chunk (l%4) ^ ((l/16)%4).
+// lane.  One instruction copies 1 KiB (16 tile rows) linearly: the hardware places lane l at
+// byte 16*l of that KiB, and the block in memory already has the LDS tile's chunk order.
 struct TileLoader {
   static constexpr int kLoads = kTileBytes / 1024 / 4;      // per wavefront
   const uint16_t* src;           // this lane's chunk in k-slice 0 of load 0
 
   __device__ __forceinline__ void init(const uint16_t* base, int tile, int kb, int wave, int lane) {
-    src = base + (int64_t)tile * kb * kBlkElems + (wave * 16 + (lane >> 2)) * kBK +
-          (((lane & 3) ^ ((lane >> 4) & 3)) << 3);
+    src = base + (int64_t)tile * kb * kBlkElems + wave * (16 * kBK) + lane * 8;
   }
   __device__ __forceinline__ void issue(char* lds_tile, int kt, int wave) const {
     const uint16_t* p = src + (int64_t)kt * kBlkElems;

@@ -43,7 +43,8 @@ class SelectParams:
 
 
 def library_path():
-    return os.path.join(_PKG_DIR, _LIB_NAME)
+    # NAT_HIP_LIBRARY selects another build of the same library (A/B timing of kernel variants)
+    return os.environ.get("NAT_HIP_LIBRARY") or os.path.join(_PKG_DIR, _LIB_NAME)
 
 
 def load_library():

@@ -10,6 +10,9 @@ Modules
   select   token selection: URS (Sec. 3.1), RPC (Sec. 4, Eq. 7-8, uniform and
            minimum-cutoff variants), deterministic truncation (Sec. 4),
            Horvitz-Thompson weights (Eq. 6, Eq. 9) and mask compaction
+  schedule general cut-length distributions q_i and their survival function
+           (Sec. 4, Eq. 7-9), Poisson sampling with given inclusion probabilities
+           (Sec. 3.1, Eq. 6), prefix packing of the truncated batch (Sec. 4)
   grpo     group-relative advantage (Eq. 2), ratio (Eq. 1), clipped surrogate
            (Eq. 3), sequence-mean objective (Eq. 5) and its gradient w.r.t.
            hidden states and the LM-head matrix (App. A)

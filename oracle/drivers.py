@@ -10,6 +10,7 @@ import itertools
 import numpy as np
 
 from . import select as sel
+from . import schedule as sch
 from . import grpo
 
 
@@ -83,6 +84,40 @@ def enumerate_rpc(batch, C=1, eps_lo=0.2, eps_hi=0.2):
         for i, L in enumerate(cuts):
             prob /= len(ranges[i])
             m[cu[i]:cu[i] + L] = True
+        _accumulate(acc, prob, estimate(batch, m, pi, eps_lo, eps_hi))
+    return acc
+
+
+def enumerate_schedule(batch, weights, eps_lo=0.2, eps_hi=0.2):
+    """Exact expectation over every combination of cuts L_i ~ q_i, q_i given by
+    integer weights per response position (Sec. 4, Eq. 7-9), rollouts independent."""
+    cu = np.asarray(batch["cu_seqlens"], dtype=np.int64)
+    per = [[int(x) for x in weights[cu[i]:cu[i + 1]]] for i in range(len(cu) - 1)]
+    pi = np.concatenate([sch.schedule_pi(a) for a in per])
+    qs = [sch.schedule_q(a) for a in per]
+    acc = {}
+    for cuts in itertools.product(*[range(1, len(a) + 1) for a in per]):
+        prob = 1.0
+        m = np.zeros(int(cu[-1]), dtype=bool)
+        for i, L in enumerate(cuts):
+            prob *= qs[i][L - 1]
+            m[cu[i]:cu[i] + L] = True
+        if prob == 0.0:
+            continue
+        _accumulate(acc, prob, estimate(batch, m, pi, eps_lo, eps_hi))
+    return acc
+
+
+def enumerate_poisson(batch, pi, eps_lo=0.2, eps_hi=0.2):
+    """Exact expectation over all 2**N independent masks m_n ~ Bernoulli(pi_n) (Sec. 3.1)."""
+    pi = np.asarray(pi, dtype=np.float64)
+    N = len(pi)
+    acc = {}
+    for bits in itertools.product((False, True), repeat=N):
+        m = np.array(bits, dtype=bool)
+        prob = float(np.prod(np.where(m, pi, 1.0 - pi)))
+        if prob == 0.0:
+            continue
         _accumulate(acc, prob, estimate(batch, m, pi, eps_lo, eps_hi))
     return acc
 

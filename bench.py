@@ -52,12 +52,14 @@ def parse_args():
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--workload", default="qwen3_8b_head_rpc")
     ap.add_argument("--scheme", default=None,
-                    help="rpc | urs | full | det | mixed (even prompts URS, odd prompts Det.Trunc. 50%%); "
+                    help="rpc | urs | full | det | schedule | poisson | mixed (even prompts URS, odd prompts Det.Trunc. 50%%); "
                          "default: the workload's own")
     ap.add_argument("--p", type=float, default=0.5)
     ap.add_argument("--min-cut", type=int, default=1)
     ap.add_argument("--seed", type=int, default=2000)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--prefix-pack", action="store_true",
+                    help="also build the truncated batch (prompt + kept prefix) each step; prefix schemes only")
     ap.add_argument("--prompts", type=int, default=None, help="override the number of prompts (smaller batch)")
     ap.add_argument("--stress-select", type=int, default=0, metavar="LOG2_TOKENS",
                     help="instead of the loss benchmark: time nat_select / nat_compact alone on 2^LOG2_TOKENS tokens")
@@ -151,6 +153,26 @@ def stress_select(args):
         out[name] = dict(tokens=N, kept=nk, select_ms=sel_ms, compact_ms=cmp_ms,
                          select_GBps=(N / 8) / sel_ms / 1e6, compact_GBps=(N / 8 + 12.0 * nk) / cmp_ms / 1e6,
                          select_Gtok_per_s=N / sel_ms / 1e6, compact_Gtok_per_s=N / cmp_ms / 1e6)
+    # widened selection stage: cut schedules (4 B read + 8 B written per token + mask), Poisson sampling
+    # (8 B read per token + mask), weights from probabilities, prefix packing (8 B per row + 4 B per kept token)
+    pi = torch.empty(N, dtype=torch.float64, device=dev)
+    weights = torch.ones(N, dtype=torch.int32, device=dev)
+    params = nat.SelectParams(nat.FULL, seed=3)
+    sch_ms = timed(lambda: nat.nat_select_schedule(params, weights, cu, B, N, cut_len, mask, pi))
+    cmp_ms = timed(lambda: nat.nat_compact_pi(B, mask, pi, cu, B, N, kept_idx, kept_seq, kept_w, cu_kept, n_kept,
+                                              None, ws))
+    nk = int(n_kept.item())
+    out["schedule"] = dict(tokens=N, kept=nk, select_ms=sch_ms, compact_ms=cmp_ms,
+                           select_GBps=(12.125 * N) / sch_ms / 1e6,
+                           compact_GBps=(N / 8 + 20.0 * nk) / cmp_ms / 1e6)
+    cu_packed, cu_loss, totals = (torch.empty(n, dtype=torch.int32, device=dev) for n in (B + 1, B + 1, 2))
+    pack_ms = timed(lambda: nat.nat_prefix_pack(None, cu, cut_len, B, 0, N, N, cu_packed, cu_loss, kept_idx, kept_seq,
+                                                src, totals, None))
+    rows = int(totals[0].item())
+    out["prefix_pack"] = dict(rows=rows, ms=pack_ms, GBps=12.0 * rows / pack_ms / 1e6)
+    pi.uniform_(0.05, 1.0)
+    poi_ms = timed(lambda: nat.nat_select_poisson(params, pi, cu, B, N, mask))
+    out["poisson"] = dict(tokens=N, select_ms=poi_ms, select_GBps=(8.125 * N) / poi_ms / 1e6)
     print(json.dumps({"metric": "nat_select / nat_compact on an inflated batch", "n_gpus": 1, "data": "synthetic",
                       "config": {"workload": f"2^{args.stress_select} tokens in {B} rollouts"}, **out}))
 
@@ -182,7 +204,8 @@ def main():
     default_scheme = {"qwen3_8b_head_rpc": "rpc", "qwen3_0p6b_head": "urs", "qwen3_8b_long_cot": "urs",
                       "wide_head_stress": "mixed", "tiny_fp32": "urs"}[args.workload]
     scheme_name = args.scheme or default_scheme
-    scheme_code = dict(full=nat.FULL, urs=nat.URS, rpc=nat.RPC, det=nat.DET, mixed=nat.URS)[scheme_name]
+    scheme_code = dict(full=nat.FULL, urs=nat.URS, rpc=nat.RPC, det=nat.DET, mixed=nat.URS,
+                       schedule=nat.FULL, poisson=nat.FULL)[scheme_name]
 
     args.scheme_name = scheme_name
     batch = si.make_batch_torch(args.workload, args.seed, dev, P=args.prompts)
@@ -198,10 +221,24 @@ def main():
     dW = torch.empty((V, H), dtype=torch.float32, device=dev)
     dtype_code = nat.DTYPE_BF16 if batch["dtype"] == "bf16" else nat.DTYPE_F32
 
+    # widened selection: a cut-length schedule with a point mass on the full length (survival >= 1/3), or
+    # token-dependent inclusion probabilities; optionally the truncated batch for the model body
+    sched_w = poisson_pi = prompt_len = None
+    if scheme_name == "schedule":
+        sched_w = torch.from_numpy(si.draw_schedule_weights(batch["lengths"], "tail_mass", args.seed).view(np.int32)).to(dev)
+    if scheme_name == "poisson":
+        poisson_pi = torch.from_numpy(si.draw_inclusion_probs(N, args.seed)).to(dev)
+    if args.prefix_pack:
+        plen = si.draw_prompt_lengths(B, args.seed)
+        prompt_len, rows_cap = torch.from_numpy(plen).to(dev), int(plen.sum()) + N
+
     def step(step_no):
         params.step = step_no
         adv = stage.advantage(rewards, P, G)
-        sc = stage.select_compact(params, cu, B, N, hidden=batch["hidden"], ids=batch["ids"], old_logp=old_logp)
+        sc = stage.select_compact(params, cu, B, N, hidden=batch["hidden"], ids=batch["ids"], old_logp=old_logp,
+                                  schedule_weights=sched_w, poisson_pi=poisson_pi)
+        if args.prefix_pack:
+            stage.prefix_pack(prompt_len, cu, sc["cut_len"], B, N, rows_cap, 1)
         nk = sc["n_kept"]
         out = stage.loss(sc["hidden_k"], batch["W"], sc["ids_k"], sc["old_logp_k"], adv, sc["kept_seq"], sc["kept_w"],
                          nk, dW=dW, want_logp=True)
@@ -265,7 +302,7 @@ def main():
         "roofline": roofline,
         "kernels": kernels,
     }
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and scheme_name not in ("schedule", "poisson"):
         result["cpu_baseline"] = cpu_baseline(batch, old_logp, scheme_code, args, torch)
     print(json.dumps(result))
 

@@ -135,6 +135,90 @@ nat_status nat_compact(const nat_select_params* params, int32_t n_rollouts_globa
                        void* d_ws, size_t ws_bytes, void* stream);
 
 /*
+ * Cut every rollout by its own cut-length distribution (Sec. 4, Eq. 7-8: L_i ~ q_i,
+ * mask 1{t <= L_i}, survival p_{i,t} = sum_{l >= t} q_i(l)).
+ *   d_weights [N] uint32: non-negative integer weights a_{i,l}, one per response
+ *             position, packed like the tokens; q_i(l) = a_{i,l} / A_i, A_i = sum_l a_{i,l}.
+ *             The last weight of a rollout should be positive so that p_{i,T_i} > 0.
+ *             A rollout whose weights are all zero is kept whole with p = 1.
+ *   The cut is the first l whose running sum exceeds r = (u64 * A_i) >> 64, u64 built
+ *   from two words of one Philox block (stream 2) keyed by (seed, step, global rollout
+ *   id); only seed, step and rollout_id_base of `params` are read.
+ *   d_cut_len [B] int32 out: L_i;  d_mask_bits as in nat_select;
+ *   d_pi      [N] double out: p_{i,t} = (sum_{l >= t} a_{i,l}) / A_i (one fp64 division of
+ *             exact integers) for EVERY position, kept or not.
+ * Errors: NULL pointer, B <= 0, N < 0 or N >= 2^31 -> NAT_INVALID_ARG.
+ */
+nat_status nat_select_schedule(const nat_select_params* params, const uint32_t* d_weights,
+                               const int64_t* d_cu_seqlens, int32_t B, int64_t N,
+                               int32_t* d_cut_len, uint32_t* d_mask_bits, double* d_pi, void* stream);
+
+/*
+ * Independent masks m_{i,t} ~ Bernoulli(p_{i,t}) with caller-supplied, token-dependent
+ * inclusion probabilities (Sec. 3.1 "Random masking"; the information-aware extension
+ * named in the discussion section).
+ *   d_pi [N] double in [0,1]: keep iff u32 < floor(p * 2^32), with the same random words
+ *        as NAT_SCHEME_URS (a constant p reproduces URS exactly).  Values <= 0 (or NaN)
+ *        never keep, values >= 1 always keep.  Tokens with p = 0 make the estimator
+ *        biased (Prop. 1 needs p > 0): that is the caller's choice.
+ * Only seed, step and rollout_id_base of `params` are read.  Errors as nat_select_schedule.
+ */
+nat_status nat_select_poisson(const nat_select_params* params, const double* d_pi,
+                              const int64_t* d_cu_seqlens, int32_t B, int64_t N,
+                              uint32_t* d_mask_bits, void* stream);
+
+/*
+ * nat_compact for masks drawn with explicit inclusion probabilities (nat_select_schedule,
+ * nat_select_poisson): identical outputs, but the weight of Eq. 6 / Eq. 9 is
+ *     kept_w = 1 / ((n_rollouts_global * T_i) * d_pi[n])
+ * (integer product, one fp64 multiplication, one fp64 division, rounded to fp32).
+ * Workspace: nat_compact_workspace_bytes(N).  Errors as nat_compact.
+ */
+nat_status nat_compact_pi(int32_t n_rollouts_global, const uint32_t* d_mask_bits, const double* d_pi,
+                          const int64_t* d_cu_seqlens, int32_t B, int64_t N,
+                          int32_t* d_kept_idx, int32_t* d_kept_seq, float* d_kept_w, int32_t* d_cu_kept,
+                          int32_t* d_n_kept, int32_t* h_n_kept,
+                          const void* d_hidden, void* d_hidden_k, int32_t H, int32_t dtype,
+                          const int32_t* d_ids, int32_t* d_ids_k,
+                          const float* d_old_logp, float* d_old_logp_k,
+                          void* d_ws, size_t ws_bytes, void* stream);
+
+/*
+ * Truncated batch for a model body that runs only over the kept prefixes (Sec. 4,
+ * "prefix structure enables true forward truncation"): rollout i becomes its P_i prompt
+ * tokens followed by its first L_i response tokens.
+ *   d_prompt_len [B] int32 or NULL (no prompts: P_i = 0);
+ *   d_cu_seqlens [B+1] int64 response-token offsets as in nat_select;
+ *   d_cut_len    [B] int32 from nat_select / nat_select_schedule (values outside [0, T_i]
+ *                are clamped);
+ *   next_token_shift: 1 = the row that scores response token t is the row before it
+ *                (next-token prediction; every P_i must be >= 1), 0 = its own row;
+ *   rows_cap:    capacity of the per-row outputs; sum_i (P_i + T_i) always suffices;
+ *   d_cu_packed  [B+1] int32 out: row offsets of the truncated sequences;
+ *   d_cu_loss    [B+1] int32 out: offsets of the kept response tokens (= sum of L_j);
+ *   d_src_idx    [rows_cap] int32 out: for each truncated row, its row in the full packed
+ *                input (prompt and response of rollout 0, then of rollout 1, ...);
+ *   d_position_ids [rows_cap] int32 out: 0 .. P_i + L_i - 1 within each sequence;
+ *   d_loss_row   [kept_cap] int32 out: truncated row whose output scores kept response
+ *                token k (ascending (i, t), the order of nat_compact); kept_cap >= sum L_i
+ *                (N always suffices);
+ *   d_totals     [2] int32 out: number of truncated rows, longest truncated sequence;
+ *   h_totals     optional PINNED host int32[2] receiving the same by an asynchronous copy;
+ *   d_input_ids -> d_input_ids_packed: optional gather of the full input's token ids
+ *                ([sum_i (P_i + T_i)] -> [rows_cap]); both NULL to skip.
+ * Rows beyond rows_cap / kept_cap are not written.
+ * Errors: NULL required pointer, B <= 0, rows_cap < 0, kept_cap < 0, shift not 0/1,
+ * shift = 1 without prompt lengths -> NAT_INVALID_ARG.
+ */
+nat_status nat_prefix_pack(const int32_t* d_prompt_len, const int64_t* d_cu_seqlens,
+                           const int32_t* d_cut_len, int32_t B, int32_t next_token_shift,
+                           int64_t rows_cap, int64_t kept_cap,
+                           int32_t* d_cu_packed, int32_t* d_cu_loss, int32_t* d_src_idx,
+                           int32_t* d_position_ids, int32_t* d_loss_row, int32_t* d_totals,
+                           int32_t* h_totals, const int32_t* d_input_ids, int32_t* d_input_ids_packed,
+                           void* stream);
+
+/*
  * Workspace for nat_loss_fwd_bwd.  *_bytes is the recommended size (largest
  * token chunk the kernels use); *_min_bytes the smallest size accepted (one
  * token tile per chunk).  Both return 0 for unsupported arguments.

@@ -71,6 +71,15 @@ def load_library():
     lib.nat_compact.restype = i32
     lib.nat_compact.argtypes = [pp, i32, vp, vp, i32, i64, vp, vp, vp, vp, vp, vp, vp, vp, i32, i32,
                                 vp, vp, vp, vp, vp, sz, vp]
+    lib.nat_select_schedule.restype = i32
+    lib.nat_select_schedule.argtypes = [pp, vp, vp, i32, i64, vp, vp, vp, vp]
+    lib.nat_select_poisson.restype = i32
+    lib.nat_select_poisson.argtypes = [pp, vp, vp, i32, i64, vp, vp]
+    lib.nat_compact_pi.restype = i32
+    lib.nat_compact_pi.argtypes = [i32, vp, vp, vp, i32, i64, vp, vp, vp, vp, vp, vp, vp, vp, i32, i32,
+                                   vp, vp, vp, vp, vp, sz, vp]
+    lib.nat_prefix_pack.restype = i32
+    lib.nat_prefix_pack.argtypes = [vp, vp, vp, i32, i32, i64, i64, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
     for name in ("nat_loss_workspace_bytes", "nat_loss_workspace_min_bytes"):
         getattr(lib, name).restype = sz
         getattr(lib, name).argtypes = [i32, i32, i32, i32]
@@ -161,6 +170,50 @@ def nat_compact(params, n_rollouts_global, mask_bits, cu_seqlens, B, N, kept_idx
         _ptr(kept_w), _ptr(cu_kept), _ptr(n_kept), _ptr(h_n_kept), _ptr(hidden), _ptr(hidden_k), H, dt,
         _ptr(ids), _ptr(ids_k), _ptr(old_logp), _ptr(old_logp_k), _ptr(workspace),
         workspace.numel() * workspace.element_size() if workspace is not None else 0, _stream()), "nat_compact")
+
+
+def nat_select_schedule(params, weights, cu_seqlens, B, N, cut_len_out, mask_bits_out, pi_out):
+    _check(cu_seqlens, torch.int64, "cu_seqlens")
+    _check(weights, torch.int32, "weights")          # the 32 bits are read as unsigned
+    _check(cut_len_out, torch.int32, "cut_len_out")
+    _check(mask_bits_out, torch.int32, "mask_bits_out")
+    _check(pi_out, torch.float64, "pi_out")
+    c = params._c()
+    _raise(load_library().nat_select_schedule(ctypes.byref(c), _ptr(weights), _ptr(cu_seqlens), B, N,
+                                              _ptr(cut_len_out), _ptr(mask_bits_out), _ptr(pi_out), _stream()),
+           "nat_select_schedule")
+
+
+def nat_select_poisson(params, pi, cu_seqlens, B, N, mask_bits_out):
+    _check(cu_seqlens, torch.int64, "cu_seqlens")
+    _check(pi, torch.float64, "pi")
+    _check(mask_bits_out, torch.int32, "mask_bits_out")
+    c = params._c()
+    _raise(load_library().nat_select_poisson(ctypes.byref(c), _ptr(pi), _ptr(cu_seqlens), B, N,
+                                             _ptr(mask_bits_out), _stream()), "nat_select_poisson")
+
+
+def nat_compact_pi(n_rollouts_global, mask_bits, pi, cu_seqlens, B, N, kept_idx, kept_seq, kept_w, cu_kept,
+                   n_kept, h_n_kept, workspace, hidden=None, hidden_k=None, ids=None, ids_k=None,
+                   old_logp=None, old_logp_k=None):
+    _check(pi, torch.float64, "pi")
+    H = hidden.shape[1] if hidden is not None else 0
+    dt = _dtype_code(hidden) if hidden is not None else DTYPE_F32
+    _raise(load_library().nat_compact_pi(
+        n_rollouts_global, _ptr(mask_bits), _ptr(pi), _ptr(cu_seqlens), B, N, _ptr(kept_idx), _ptr(kept_seq),
+        _ptr(kept_w), _ptr(cu_kept), _ptr(n_kept), _ptr(h_n_kept), _ptr(hidden), _ptr(hidden_k), H, dt,
+        _ptr(ids), _ptr(ids_k), _ptr(old_logp), _ptr(old_logp_k), _ptr(workspace),
+        workspace.numel() * workspace.element_size() if workspace is not None else 0, _stream()), "nat_compact_pi")
+
+
+def nat_prefix_pack(prompt_len, cu_seqlens, cut_len, B, next_token_shift, rows_cap, kept_cap, cu_packed, cu_loss,
+                    src_idx, position_ids, loss_row, totals, h_totals, input_ids=None, input_ids_packed=None):
+    _check(cu_seqlens, torch.int64, "cu_seqlens")
+    _check(cut_len, torch.int32, "cut_len")
+    _raise(load_library().nat_prefix_pack(
+        _ptr(prompt_len), _ptr(cu_seqlens), _ptr(cut_len), B, int(next_token_shift), int(rows_cap), int(kept_cap),
+        _ptr(cu_packed), _ptr(cu_loss), _ptr(src_idx), _ptr(position_ids), _ptr(loss_row), _ptr(totals),
+        _ptr(h_totals), _ptr(input_ids), _ptr(input_ids_packed), _stream()), "nat_prefix_pack")
 
 
 def nat_loss_fwd_bwd(hidden_k, W, ids_k, old_logp_k, adv, kept_seq, kept_w, N_k, eps_lo, eps_hi, grad_scale,

@@ -1,6 +1,8 @@
-// nat_compact: stable mask -> index compaction of the selected tokens with the
-// Horvitz-Thompson weight of Eq. 6 / Eq. 9 folded with the 1/G * 1/|o_i|
-// averaging of Eq. 5, plus an optional gather of the kept rows.
+// nat_compact / nat_compact_pi: stable mask -> index compaction of the selected
+// tokens with the Horvitz-Thompson weight of Eq. 6 / Eq. 9 folded with the
+// 1/G * 1/|o_i| averaging of Eq. 5 (inclusion probability from the scheme's
+// closed form, or read from a per-token array), plus an optional gather of the
+// kept rows.
 //
 // Three passes over the bit mask: per-tile population counts, an exclusive scan
 // of the tile counts, and a scatter in which each wavefront ranks its 64 tokens
@@ -12,15 +14,6 @@ namespace nat {
 constexpr int kTileTokens = 4096;                 // tokens per scatter block
 constexpr int kTileWords = kTileTokens / 32;      // 128 mask words
 constexpr int kScatterThreads = 256;              // 4 wavefronts x 1024 tokens
-
-// last i in [lo, hi) with cu[i] <= n; the caller guarantees cu[lo] <= n < cu[hi]
-__device__ __forceinline__ int rollout_of_pos(const int64_t* __restrict__ cu, int lo, int hi, int64_t n) {
-  while (hi - lo > 1) {
-    const int mid = (lo + hi) >> 1;
-    if (cu[mid] <= n) lo = mid; else hi = mid;
-  }
-  return lo;
-}
 
 __device__ __forceinline__ int wave_sum(int v) {
   for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off);
@@ -88,7 +81,8 @@ __device__ __forceinline__ float ht_weight(int scheme, int64_t T, int64_t t, dou
 }
 
 __global__ void __launch_bounds__(kScatterThreads)
-compact_scatter_kernel(SelectArgs a, double n_rollouts, const uint32_t* __restrict__ mask_bits, int64_t n_words,
+compact_scatter_kernel(SelectArgs a, double n_rollouts, const double* __restrict__ pi,
+                       const uint32_t* __restrict__ mask_bits, int64_t n_words,
                        const int64_t* __restrict__ cu, int B, const int32_t* __restrict__ tile_offset,
                        int32_t* __restrict__ kept_idx, int32_t* __restrict__ kept_seq, float* __restrict__ kept_w) {
   __shared__ int wave_cnt[4];
@@ -127,7 +121,8 @@ compact_scatter_kernel(SelectArgs a, double n_rollouts, const uint32_t* __restri
       const int out = base + rank;
       kept_idx[out] = (int32_t)n;
       kept_seq[out] = i;
-      kept_w[out] = ht_weight(scheme, T, n - start + 1, n_rollouts, a.p, a.min_cut);
+      kept_w[out] = pi ? (float)(1.0 / ((n_rollouts * (double)T) * pi[n]))
+                       : ht_weight(scheme, T, n - start + 1, n_rollouts, a.p, a.min_cut);
     }
     base += __popcll(group);
   }
@@ -182,6 +177,61 @@ extern "C" size_t nat_compact_workspace_bytes(int64_t N) {
   return ((ints * sizeof(int32_t) + 255) / 256) * 256 + 256;
 }
 
+namespace nat {
+
+nat_status compact_run(const SelectArgs& a, const CompactArgs& c) {
+  if (!c.cu || !c.cu_kept || !c.n_kept || c.B <= 0 || c.N < 0 || c.N >= (int64_t(1) << 31) ||
+      c.n_rollouts_global <= 0)
+    return NAT_INVALID_ARG;
+  if (c.N > 0 && (!c.mask_bits || !c.kept_idx || !c.kept_seq || !c.kept_w)) return NAT_INVALID_ARG;
+  if ((c.hidden != nullptr) != (c.hidden_k != nullptr) || (c.ids != nullptr) != (c.ids_k != nullptr) ||
+      (c.old_logp != nullptr) != (c.old_logp_k != nullptr))
+    return NAT_INVALID_ARG;
+  int64_t row_bytes = 0;
+  if (c.hidden) {
+    if (c.dtype != NAT_DTYPE_F32 && c.dtype != NAT_DTYPE_BF16) return NAT_UNSUPPORTED_DTYPE;
+    if (c.H <= 0) return NAT_BAD_SHAPE;
+    row_bytes = (int64_t)c.H * (c.dtype == NAT_DTYPE_F32 ? 4 : 2);
+    if (row_bytes % 16 != 0) return NAT_BAD_SHAPE;
+  }
+  if (!c.ws || c.ws_bytes < nat_compact_workspace_bytes(c.N)) return NAT_WORKSPACE_TOO_SMALL;
+
+  hipStream_t s = c.stream;
+  const int64_t n_tiles = n_tiles_of(c.N);
+  const int64_t n_words = nat_mask_words(c.N);
+  int32_t* tile_count = (int32_t*)c.ws;
+  int32_t* tile_offset = tile_count + n_tiles;
+  {
+    ProfScope prof(PC_COMPACT, s);
+    if (n_tiles > 0) {
+      compact_count_kernel<<<(unsigned)n_tiles, kTileWords, 0, s>>>(c.mask_bits, n_words, tile_count);
+      NAT_LAUNCH_CHECK();
+    }
+    compact_scan_kernel<<<1, 1024, 0, s>>>(tile_count, (int)n_tiles, tile_offset, c.n_kept);
+    NAT_LAUNCH_CHECK();
+    if (n_tiles > 0) {
+      compact_scatter_kernel<<<(unsigned)n_tiles, kScatterThreads, 0, s>>>(
+          a, (double)c.n_rollouts_global, c.pi, c.mask_bits, n_words, c.cu, c.B, tile_offset,
+          c.kept_idx, c.kept_seq, c.kept_w);
+      NAT_LAUNCH_CHECK();
+    }
+    compact_cu_kept_kernel<<<(c.B + 1 + 255) / 256, 256, 0, s>>>(c.mask_bits, c.cu, c.B, tile_offset, c.cu_kept);
+    NAT_LAUNCH_CHECK();
+  }
+  if (c.h_n_kept) NAT_HIP_TRY(hipMemcpyAsync(c.h_n_kept, c.n_kept, sizeof(int32_t), hipMemcpyDeviceToHost, s));
+  if (c.N > 0 && (c.hidden || c.ids || c.old_logp)) {
+    ProfScope prof(PC_GATHER, s);
+    const int64_t grid = c.N < 65536 * 4 ? c.N : 65536 * 4;
+    gather_rows_kernel<<<(unsigned)grid, 256, 0, s>>>(c.kept_idx, c.n_kept, c.N, (const uint4*)c.hidden,
+                                                     (uint4*)c.hidden_k, row_bytes / 16, c.ids, c.ids_k,
+                                                     c.old_logp, c.old_logp_k);
+    NAT_LAUNCH_CHECK();
+  }
+  return NAT_OK;
+}
+
+}  // namespace nat
+
 extern "C" nat_status nat_compact(const nat_select_params* params, int32_t n_rollouts_global,
                                   const uint32_t* d_mask_bits, const int64_t* d_cu_seqlens, int32_t B, int64_t N,
                                   int32_t* d_kept_idx, int32_t* d_kept_seq, float* d_kept_w, int32_t* d_cu_kept,
@@ -193,52 +243,27 @@ extern "C" nat_status nat_compact(const nat_select_params* params, int32_t n_rol
   SelectArgs a;
   nat_status st = validate_select(params, &a);
   if (st != NAT_OK) return st;
-  if (!d_cu_seqlens || !d_cu_kept || !d_n_kept || B <= 0 || N < 0 || N >= (int64_t(1) << 31) ||
-      n_rollouts_global <= 0)
-    return NAT_INVALID_ARG;
-  if (N > 0 && (!d_mask_bits || !d_kept_idx || !d_kept_seq || !d_kept_w)) return NAT_INVALID_ARG;
-  if ((d_hidden != nullptr) != (d_hidden_k != nullptr) || (d_ids != nullptr) != (d_ids_k != nullptr) ||
-      (d_old_logp != nullptr) != (d_old_logp_k != nullptr))
-    return NAT_INVALID_ARG;
-  int64_t row_bytes = 0;
-  if (d_hidden) {
-    if (dtype != NAT_DTYPE_F32 && dtype != NAT_DTYPE_BF16) return NAT_UNSUPPORTED_DTYPE;
-    if (H <= 0) return NAT_BAD_SHAPE;
-    row_bytes = (int64_t)H * (dtype == NAT_DTYPE_F32 ? 4 : 2);
-    if (row_bytes % 16 != 0) return NAT_BAD_SHAPE;
-  }
-  if (!d_ws || ws_bytes < nat_compact_workspace_bytes(N)) return NAT_WORKSPACE_TOO_SMALL;
+  return compact_run(a, CompactArgs{n_rollouts_global, d_mask_bits, nullptr, d_cu_seqlens, B, N, d_kept_idx,
+                                    d_kept_seq, d_kept_w, d_cu_kept, d_n_kept, h_n_kept, d_hidden, d_hidden_k, H,
+                                    dtype, d_ids, d_ids_k, d_old_logp, d_old_logp_k, d_ws, ws_bytes,
+                                    (hipStream_t)stream});
+}
 
-  hipStream_t s = (hipStream_t)stream;
-  const int64_t n_tiles = n_tiles_of(N);
-  const int64_t n_words = nat_mask_words(N);
-  int32_t* tile_count = (int32_t*)d_ws;
-  int32_t* tile_offset = tile_count + n_tiles;
-  {
-    ProfScope prof(PC_COMPACT, s);
-    if (n_tiles > 0) {
-      compact_count_kernel<<<(unsigned)n_tiles, kTileWords, 0, s>>>(d_mask_bits, n_words, tile_count);
-      NAT_LAUNCH_CHECK();
-    }
-    compact_scan_kernel<<<1, 1024, 0, s>>>(tile_count, (int)n_tiles, tile_offset, d_n_kept);
-    NAT_LAUNCH_CHECK();
-    if (n_tiles > 0) {
-      compact_scatter_kernel<<<(unsigned)n_tiles, kScatterThreads, 0, s>>>(
-          a, (double)n_rollouts_global, d_mask_bits, n_words, d_cu_seqlens, B, tile_offset,
-          d_kept_idx, d_kept_seq, d_kept_w);
-      NAT_LAUNCH_CHECK();
-    }
-    compact_cu_kept_kernel<<<(B + 1 + 255) / 256, 256, 0, s>>>(d_mask_bits, d_cu_seqlens, B, tile_offset, d_cu_kept);
-    NAT_LAUNCH_CHECK();
-  }
-  if (h_n_kept) NAT_HIP_TRY(hipMemcpyAsync(h_n_kept, d_n_kept, sizeof(int32_t), hipMemcpyDeviceToHost, s));
-  if (N > 0 && (d_hidden || d_ids || d_old_logp)) {
-    ProfScope prof(PC_GATHER, s);
-    const int64_t grid = N < 65536 * 4 ? N : 65536 * 4;
-    gather_rows_kernel<<<(unsigned)grid, 256, 0, s>>>(d_kept_idx, d_n_kept, N, (const uint4*)d_hidden,
-                                                     (uint4*)d_hidden_k, row_bytes / 16, d_ids, d_ids_k,
-                                                     d_old_logp, d_old_logp_k);
-    NAT_LAUNCH_CHECK();
-  }
-  return NAT_OK;
+extern "C" nat_status nat_compact_pi(int32_t n_rollouts_global, const uint32_t* d_mask_bits, const double* d_pi,
+                                     const int64_t* d_cu_seqlens, int32_t B, int64_t N,
+                                     int32_t* d_kept_idx, int32_t* d_kept_seq, float* d_kept_w, int32_t* d_cu_kept,
+                                     int32_t* d_n_kept, int32_t* h_n_kept,
+                                     const void* d_hidden, void* d_hidden_k, int32_t H, int32_t dtype,
+                                     const int32_t* d_ids, int32_t* d_ids_k,
+                                     const float* d_old_logp, float* d_old_logp_k,
+                                     void* d_ws, size_t ws_bytes, void* stream) {
+  if (N > 0 && !d_pi) return NAT_INVALID_ARG;
+  SelectArgs a{};
+  a.scheme = NAT_SCHEME_FULL;
+  a.min_cut = 1;
+  a.p = 1.0;
+  return compact_run(a, CompactArgs{n_rollouts_global, d_mask_bits, d_pi, d_cu_seqlens, B, N, d_kept_idx,
+                                    d_kept_seq, d_kept_w, d_cu_kept, d_n_kept, h_n_kept, d_hidden, d_hidden_k, H,
+                                    dtype, d_ids, d_ids_k, d_old_logp, d_old_logp_k, d_ws, ws_bytes,
+                                    (hipStream_t)stream});
 }

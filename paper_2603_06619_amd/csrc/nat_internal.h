@@ -10,7 +10,7 @@ namespace nat {
 // Kernel classes for the optional per-kernel timing.
 enum ProfClass : int {
   PC_ADVANTAGE = 0, PC_SELECT, PC_COMPACT, PC_GATHER, PC_TRANSPOSE, PC_LOGITS, PC_TOKEN_STATS,
-  PC_RESCALE, PC_DHIDDEN, PC_DWEIGHT, PC_LOSS_REDUCE, PC_F32_PATH, PC_FILL, PC_NUM
+  PC_RESCALE, PC_DHIDDEN, PC_DWEIGHT, PC_LOSS_REDUCE, PC_F32_PATH, PC_FILL, PC_SCHEDULE, PC_PREFIX_PACK, PC_NUM
 };
 
 // Brackets the launches issued during its lifetime with two events when timing is on.
@@ -32,6 +32,32 @@ struct SelectArgs {
   const int32_t* scheme_per_rollout;
 };
 nat_status validate_select(const nat_select_params* p, SelectArgs* out);
+
+// Rollout that contains packed position n: the last i in [lo, hi) with cu[i] <= n (skips
+// empty rollouts, whose offsets repeat).  The caller guarantees cu[lo] <= n < cu[hi].
+template <typename OffsetT>
+__device__ __forceinline__ int rollout_of_pos(const OffsetT* __restrict__ cu, int lo, int hi, int64_t n) {
+  while (hi - lo > 1) {
+    const int mid = (lo + hi) >> 1;
+    if ((int64_t)cu[mid] <= n) lo = mid; else hi = mid;
+  }
+  return lo;
+}
+
+// mask bit n = (position of n inside its rollout) < cut_len[rollout]   (select.hip)
+nat_status launch_prefix_mask(const int64_t* d_cu, int32_t B, int64_t N, const int32_t* d_cut_len,
+                              uint32_t* d_mask_bits, hipStream_t s);
+
+// nat_compact / nat_compact_pi share one implementation (compact.hip): weights come from
+// the scheme's closed form when d_pi is NULL, else from the given probabilities.
+struct CompactArgs {
+  int32_t n_rollouts_global; const uint32_t* mask_bits; const double* pi; const int64_t* cu; int32_t B; int64_t N;
+  int32_t* kept_idx; int32_t* kept_seq; float* kept_w; int32_t* cu_kept; int32_t* n_kept; int32_t* h_n_kept;
+  const void* hidden; void* hidden_k; int32_t H; int32_t dtype;
+  const int32_t* ids; int32_t* ids_k; const float* old_logp; float* old_logp_k;
+  void* ws; size_t ws_bytes; hipStream_t stream;
+};
+nat_status compact_run(const SelectArgs& sel, const CompactArgs& c);
 
 // bf16 loss path (loss_bf16.hip) and fp32 loss path (loss_f32.hip)
 struct LossArgs {

@@ -7,17 +7,6 @@
 
 namespace nat {
 
-// Rollout that contains packed position n: the last i with cu[i] <= n (skips
-// empty rollouts, whose offsets repeat).
-__device__ __forceinline__ int rollout_of(const int64_t* __restrict__ cu, int B, int64_t n) {
-  int lo = 0, hi = B;              // invariant: cu[lo] <= n < cu[hi]
-  while (hi - lo > 1) {
-    const int mid = (lo + hi) >> 1;
-    if (cu[mid] <= n) lo = mid; else hi = mid;
-  }
-  return lo;
-}
-
 __global__ void advantage_kernel(const float* __restrict__ rewards, int P, int G, float eps_adv,
                                  float* __restrict__ adv) {
   // one wavefront per prompt; fixed-order lane-strided sums then a butterfly
@@ -62,7 +51,7 @@ select_mask_kernel(SelectArgs a, const int64_t* __restrict__ cu, int B, int64_t 
   const int64_t n = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   bool keep = false;
   if (n < N) {
-    const int i = rollout_of(cu, B, n);
+    const int i = rollout_of_pos(cu, 0, B, n);
     const int64_t t0 = n - cu[i];
     const int scheme = a.scheme_per_rollout ? a.scheme_per_rollout[i] : a.scheme;
     if (scheme == NAT_SCHEME_URS) {
@@ -101,6 +90,16 @@ nat_status validate_select(const nat_select_params* p, SelectArgs* out) {
   out->step = p->step;
   out->rollout_id_base = p->rollout_id_base;
   out->scheme_per_rollout = p->d_scheme_per_rollout;
+  return NAT_OK;
+}
+
+nat_status launch_prefix_mask(const int64_t* d_cu, int32_t B, int64_t N, const int32_t* d_cut_len,
+                              uint32_t* d_mask_bits, hipStream_t s) {
+  if (N <= 0) return NAT_OK;
+  SelectArgs a{};
+  a.scheme = NAT_SCHEME_DET;        // any prefix scheme: keep t0 < cut_len[i]
+  select_mask_kernel<<<(unsigned)((N + 255) / 256), 256, 0, s>>>(a, d_cu, B, N, d_cut_len, d_mask_bits);
+  NAT_LAUNCH_CHECK();
   return NAT_OK;
 }
 

@@ -144,3 +144,61 @@ def behaviour_logp_stand_in(hidden, W, ids, logp_noise):
         wy = W[ids[a:a + step].long()].float()
         out[a:a + step] = (h * wy).sum(1) - (math.log(W.shape[0]) + 0.5 * W_STD ** 2 * (h * h).sum(1))
     return out + logp_noise
+
+
+# ---- inputs of the widened selection stage: cut-length schedules, per-token
+# ---- inclusion probabilities, prompt lengths (random draws only; what they mean
+# ---- is the selection code's business)
+
+def draw_schedule_weights(lengths, kind, seed, C=100):
+    """Packed uint32 weights a_{i,l}, one per response position.
+
+    kind: "uniform"   all ones;
+          "min_cut"   zero below position C, one from C on (zero-length prefix when C > T);
+          "tail_mass" ones, plus a point mass of T_i // 2 on the last position
+                      (the survival function stays above 1/3);
+          "random"    32-bit random values with ~25 % zeros, the last one forced positive;
+          "sparse"    all zero except three random positions and the last one.
+    """
+    rng = np.random.default_rng([seed, 7])
+    out = []
+    for T in np.asarray(lengths, dtype=np.int64):
+        T = int(T)
+        if kind == "uniform":
+            a = np.ones(T, dtype=np.uint32)
+        elif kind == "min_cut":
+            a = np.ones(T, dtype=np.uint32)
+            a[:min(max(C - 1, 0), max(T - 1, 0))] = 0
+        elif kind == "tail_mass":
+            a = np.ones(T, dtype=np.uint32)
+            if T:
+                a[-1] += T // 2
+        elif kind == "random":
+            a = rng.integers(0, 2 ** 32, T, dtype=np.uint64).astype(np.uint32)
+            a[rng.random(T) < 0.25] = 0
+            if T:
+                a[-1] |= 1
+        elif kind == "sparse":
+            a = np.zeros(T, dtype=np.uint32)
+            if T:
+                a[rng.integers(0, T, 3)] = rng.integers(1, 1000, 3)
+                a[-1] = 5
+        else:
+            raise ValueError(kind)
+        out.append(a)
+    return np.concatenate(out) if out else np.zeros(0, np.uint32)
+
+
+def draw_inclusion_probs(N, seed, floor=0.05):
+    """Per-token probabilities in [floor, 1] (fp64): a stand-in for an information-aware
+    score (e.g. normalised token entropy); ~10 % of tokens sit at exactly 1."""
+    rng = np.random.default_rng([seed, 8])
+    pi = floor + (1.0 - floor) * rng.random(N) ** 2
+    pi[rng.random(N) < 0.1] = 1.0
+    return pi
+
+
+def draw_prompt_lengths(B, seed, lo=32, hi=512):
+    """Prompt lengths P_i (int32) for B rollouts; rollouts of one prompt would share it, which
+    changes nothing for the packing code, so they are drawn independently."""
+    return np.random.default_rng([seed, 9]).integers(lo, hi + 1, B).astype(np.int32)

@@ -88,6 +88,39 @@ def test_compact_argument_errors(lib):
     assert lib.nat_compact(*args(ws=None)) == 3
 
 
+def test_schedule_poisson_and_pack_argument_errors(lib):
+    import paper_2603_06619_amd as nat
+    fake = ctypes.c_void_p(256)
+    ok = ctypes.byref(_params(nat))
+    assert lib.nat_select_schedule(None, fake, fake, 4, 10, fake, fake, fake, None) == 1
+    assert lib.nat_select_schedule(ok, None, fake, 4, 10, fake, fake, fake, None) == 1
+    assert lib.nat_select_schedule(ok, fake, None, 4, 10, fake, fake, fake, None) == 1
+    assert lib.nat_select_schedule(ok, fake, fake, 0, 10, fake, fake, fake, None) == 1
+    assert lib.nat_select_schedule(ok, fake, fake, 4, 1 << 31, fake, fake, fake, None) == 1
+    assert lib.nat_select_schedule(ok, fake, fake, 4, 10, None, fake, fake, None) == 1
+    assert lib.nat_select_schedule(ok, fake, fake, 4, 10, fake, fake, None, None) == 1
+    assert lib.nat_select_poisson(ok, None, fake, 4, 10, fake, None) == 1
+    assert lib.nat_select_poisson(ok, fake, fake, 4, -1, fake, None) == 1
+    assert lib.nat_select_poisson(ok, fake, fake, 4, 10, None, None) == 1
+    cargs = lambda **kw: [kw.get("nroll", 4), fake, kw.get("pi", fake), fake, kw.get("B", 4), 100,
+                          fake, fake, fake, fake, fake, None, None, None, 0, 0, None, None, None, None,
+                          fake, kw.get("ws_bytes", 1 << 20), None]
+    assert lib.nat_compact_pi(*cargs(pi=None)) == 1
+    assert lib.nat_compact_pi(*cargs(nroll=0)) == 1
+    assert lib.nat_compact_pi(*cargs(ws_bytes=8)) == 3
+    pargs = lambda **kw: [kw.get("P", fake), kw.get("cu", fake), fake, kw.get("B", 4), kw.get("shift", 1),
+                          kw.get("rows", 100), kw.get("kept", 50), fake, fake, kw.get("src", fake), fake, fake,
+                          kw.get("tot", fake), None, kw.get("ids", None), None, None]
+    assert lib.nat_prefix_pack(*pargs(cu=None)) == 1
+    assert lib.nat_prefix_pack(*pargs(B=0)) == 1
+    assert lib.nat_prefix_pack(*pargs(shift=2)) == 1
+    assert lib.nat_prefix_pack(*pargs(P=None, shift=1)) == 1               # next-token shift needs prompt lengths
+    assert lib.nat_prefix_pack(*pargs(rows=-1)) == 1
+    assert lib.nat_prefix_pack(*pargs(src=None)) == 1
+    assert lib.nat_prefix_pack(*pargs(tot=None)) == 1
+    assert lib.nat_prefix_pack(*pargs(ids=fake)) == 1                      # gather pair incomplete
+
+
 def test_loss_argument_errors(lib):
     fake = ctypes.c_void_p(256)
     f = ctypes.c_float

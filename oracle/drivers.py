@@ -2,7 +2,8 @@
 variances (Sec. 3.1 second moment, Sec. 4 covariance, App. B.1 and B.4).
 
 A "batch" is a dict: cu_seqlens [B+1], hidden [N, H], W [V, H], ids [N],
-old_logp [N], adv [B]  (packed response tokens of B rollouts).
+old_logp [N], adv [B]  (packed response tokens of B rollouts); optionally
+ref_logp [N], beta_kl, kl_kind for the KL term of Eq. 4.
 
 Test infrastructure: not used by the product path.
 """
@@ -36,7 +37,9 @@ def estimate(batch, mask, pi, eps_lo=0.2, eps_hi=0.2, n_rollouts=None):
     w = 1.0 / (nB * T[kept] * np.asarray(pi, dtype=np.float64)[kept])
     out = grpo.loss_and_grads(np.asarray(batch["hidden"])[kept], batch["W"],
                               np.asarray(batch["ids"])[kept], np.asarray(batch["old_logp"])[kept],
-                              np.asarray(batch["adv"], dtype=np.float64)[seq[kept]], w, eps_lo, eps_hi)
+                              np.asarray(batch["adv"], dtype=np.float64)[seq[kept]], w, eps_lo, eps_hi,
+                              ref_logp=(np.asarray(batch["ref_logp"])[kept] if "ref_logp" in batch else None),
+                              beta_kl=batch.get("beta_kl", 0.0), kl_kind=batch.get("kl_kind", grpo.KL_LOG_RATIO))
     dH = np.zeros(np.asarray(batch["hidden"]).shape, dtype=np.float64)
     dH[kept] = out["dH"]
     return dict(loss=out["loss"], dH=dH, dW=out["dW"])

@@ -58,6 +58,9 @@ def parse_args():
     ap.add_argument("--min-cut", type=int, default=1)
     ap.add_argument("--seed", type=int, default=2000)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--kl-beta", type=float, default=0.0,
+                    help="weight of the KL term of the token loss (reference log-probs are synthetic); 0 = off")
+    ap.add_argument("--entropy", action="store_true", help="also accumulate the per-token entropy in the sweep")
     ap.add_argument("--prefix-pack", action="store_true",
                     help="also build the truncated batch (prompt + kept prefix) each step; prefix schemes only")
     ap.add_argument("--prompts", type=int, default=None, help="override the number of prompts (smaller batch)")
@@ -240,8 +243,13 @@ def main():
         if args.prefix_pack:
             stage.prefix_pack(prompt_len, cu, sc["cut_len"], B, N, rows_cap, 1)
         nk = sc["n_kept"]
+        kl = {}
+        if args.kl_beta > 0 or args.entropy:
+            # reference log-probs: the behaviour log-probs stand in (only their shape matters for the timing)
+            kl = dict(ref_logp_k=sc["old_logp_k"], beta_kl=args.kl_beta, kl_kind=nat.KL_NONNEG,
+                      want_kl=args.kl_beta > 0, want_entropy=args.entropy)
         out = stage.loss(sc["hidden_k"], batch["W"], sc["ids_k"], sc["old_logp_k"], adv, sc["kept_seq"], sc["kept_w"],
-                         nk, dW=dW, want_logp=True)
+                         nk, dW=dW, want_logp=True, **kl)
         return nk, out
 
     for w in range(args.warmup):
@@ -292,7 +300,8 @@ def main():
         "vs_baseline": None, "dtype": batch["dtype"], "data": "synthetic",
         "config": {"workload": args.workload, "P": P, "G": G, "H": H, "V": V, "tokens": N,
                    "kept_tokens_per_step": kept_total / args.steps, "scheme": scheme_name,
-                   "p": args.p if scheme_name == "urs" else None, "min_cut": args.min_cut if scheme_name == "rpc" else None},
+                   "p": args.p if scheme_name == "urs" else None, "min_cut": args.min_cut if scheme_name == "rpc" else None,
+                   "kl_beta": args.kl_beta, "entropy": bool(args.entropy)},
         "mfma_util_pct_useful_6VH": 100.0 * useful_tflops / PEAK_BF16_TFLOPS,
         "mfma_util_pct_gemm_kernels_only": (100.0 * 6.0 * V * H * kept_total / (gemm_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS
                                             if gemm_ms > 0 else None),

@@ -46,6 +46,9 @@ enum {
 
 enum { NAT_SCHEME_FULL = 0, NAT_SCHEME_URS = 1, NAT_SCHEME_RPC = 2, NAT_SCHEME_DET = 3 };
 enum { NAT_DTYPE_F32 = 0, NAT_DTYPE_BF16 = 1 };
+/* sampled-token forms of the KL term of Eq. 4, with d = ref_logp - logp:
+ * LOG_RATIO: -d (the form named in the footnote to Eq. 4);  NONNEG: exp(d) - d - 1. */
+enum { NAT_KL_LOG_RATIO = 0, NAT_KL_NONNEG = 1 };
 
 /* Human-readable name of a status code (static string, never NULL). */
 const char* nat_status_string(nat_status s);
@@ -236,7 +239,7 @@ size_t nat_loss_workspace_min_bytes(int32_t N_k, int32_t H, int32_t V, int32_t d
  *     c_k = -grad_scale * kept_w[k] * dS_k/dlogp_k,  dS/dlogp = r A if (A>0 and r<=1+eps_hi)
  *                                                     or (A<0 and r>=1-eps_lo), else 0,
  *     dz_k = c_k (onehot(ids_k) - softmax(z_k)),  dH_k = W^T dz_k,  dW = sum_k dz_k h_k^T.
- * The KL term of Eq. 4 is not included (beta = 0 as in Sec. 5.1).
+ * The KL term of Eq. 4 is not included (beta = 0 as in Sec. 5.1); see nat_loss_fwd_bwd_kl.
  *   d_hidden_k [N_k, H] row-major, dtype bf16 or f32;  d_W [V, H] row-major, same dtype;
  *   d_ids_k [N_k] int32 in [0, V);  d_old_logp_k [N_k] float;  d_adv [>= max(kept_seq)+1] float;
  *   d_loss [1] float out;  d_logp_k [N_k] float out or NULL;
@@ -258,6 +261,31 @@ nat_status nat_loss_fwd_bwd(const void* d_hidden_k, const void* d_W, const int32
                             float eps_lo, float eps_hi, float grad_scale,
                             float* d_loss, float* d_logp_k, void* d_dH_k, float* d_dW,
                             int32_t accumulate_dw, void* d_ws, size_t ws_bytes, void* stream);
+
+/*
+ * nat_loss_fwd_bwd with the token loss of Eq. 4, L_k = S_k - beta_kl * KL_k, and two
+ * per-token diagnostics.  KL_k is a sampled-token estimate of D_KL(pi_theta || pi_ref)
+ * computed from d_k = d_ref_logp_k[k] - logp_k in the form `kl_kind` (NAT_KL_*):
+ *     loss = - sum_k kept_w[k] (S_k - beta_kl KL_k),
+ *     c_k  = -grad_scale * kept_w[k] * (dS_k/dlogp_k - beta_kl dKL_k/dlogp_k),
+ * everything else as nat_loss_fwd_bwd (same kernels; beta_kl = 0 gives the same bits).
+ *   d_ref_logp_k [N_k] float: log-probability of the sampled token under the reference
+ *                policy; may be NULL when beta_kl = 0;
+ *   d_kl_k       [N_k] float out or NULL: KL_k (0 when beta_kl = 0);
+ *   d_entropy_k  [N_k] float out or NULL: -sum_v p_v log p_v of the current policy at each
+ *                kept token (the quantity of the paper's entropy curves), accumulated in the
+ *                same sweep over the vocabulary; it has no gradient.
+ * Errors: as nat_loss_fwd_bwd, plus beta_kl < 0, unknown kl_kind, or beta_kl > 0 with
+ * d_ref_logp_k NULL -> NAT_INVALID_ARG.
+ */
+nat_status nat_loss_fwd_bwd_kl(const void* d_hidden_k, const void* d_W, const int32_t* d_ids_k,
+                               const float* d_old_logp_k, const float* d_adv, const int32_t* d_kept_seq,
+                               const float* d_kept_w, int32_t N_k, int32_t H, int32_t V, int32_t dtype,
+                               float eps_lo, float eps_hi, float grad_scale,
+                               const float* d_ref_logp_k, float beta_kl, int32_t kl_kind,
+                               float* d_loss, float* d_logp_k, float* d_kl_k, float* d_entropy_k,
+                               void* d_dH_k, float* d_dW, int32_t accumulate_dw,
+                               void* d_ws, size_t ws_bytes, void* stream);
 
 /*
  * Per-kernel timing (measurement aid, off by default).  When enabled, every

@@ -10,6 +10,7 @@ _lib = None
 
 FULL, URS, RPC, DET = 0, 1, 2, 3
 DTYPE_F32, DTYPE_BF16 = 0, 1
+KL_LOG_RATIO, KL_NONNEG = 0, 1
 
 
 class NatError(RuntimeError):
@@ -86,6 +87,9 @@ def load_library():
     lib.nat_loss_fwd_bwd.restype = i32
     lib.nat_loss_fwd_bwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, f32, f32, f32,
                                      vp, vp, vp, vp, i32, vp, sz, vp]
+    lib.nat_loss_fwd_bwd_kl.restype = i32
+    lib.nat_loss_fwd_bwd_kl.argtypes = [vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, f32, f32, f32,
+                                        vp, f32, i32, vp, vp, vp, vp, vp, vp, i32, vp, sz, vp]
     lib.nat_profile_num_classes.restype = i32
     lib.nat_profile_class_name.restype = ctypes.c_char_p
     lib.nat_profile_class_name.argtypes = [i32]
@@ -224,6 +228,19 @@ def nat_loss_fwd_bwd(hidden_k, W, ids_k, old_logp_k, adv, kept_seq, kept_w, N_k,
         N_k, H, V, _dtype_code(W), eps_lo, eps_hi, grad_scale, _ptr(loss_out), _ptr(logp_out), _ptr(dH_out),
         _ptr(dW_out), int(accumulate_dw), _ptr(workspace),
         workspace.numel() * workspace.element_size() if workspace is not None else 0, _stream()), "nat_loss_fwd_bwd")
+
+
+def nat_loss_fwd_bwd_kl(hidden_k, W, ids_k, old_logp_k, adv, kept_seq, kept_w, N_k, eps_lo, eps_hi, grad_scale,
+                        ref_logp_k, beta_kl, kl_kind, loss_out, logp_out, kl_out, entropy_out, dH_out, dW_out,
+                        accumulate_dw, workspace):
+    V, H = W.shape
+    _raise(load_library().nat_loss_fwd_bwd_kl(
+        _ptr(hidden_k), _ptr(W), _ptr(ids_k), _ptr(old_logp_k), _ptr(adv), _ptr(kept_seq), _ptr(kept_w),
+        N_k, H, V, _dtype_code(W), eps_lo, eps_hi, grad_scale, _ptr(ref_logp_k), float(beta_kl), int(kl_kind),
+        _ptr(loss_out), _ptr(logp_out), _ptr(kl_out), _ptr(entropy_out), _ptr(dH_out), _ptr(dW_out),
+        int(accumulate_dw), _ptr(workspace),
+        workspace.numel() * workspace.element_size() if workspace is not None else 0, _stream()),
+        "nat_loss_fwd_bwd_kl")
 
 
 def profile_enable(on):

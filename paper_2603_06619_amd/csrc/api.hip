@@ -121,19 +121,23 @@ extern "C" size_t nat_loss_workspace_min_bytes(int32_t N_k, int32_t H, int32_t V
   return 0;
 }
 
-extern "C" nat_status nat_loss_fwd_bwd(const void* d_hidden_k, const void* d_W, const int32_t* d_ids_k,
-                                       const float* d_old_logp_k, const float* d_adv, const int32_t* d_kept_seq,
-                                       const float* d_kept_w, int32_t N_k, int32_t H, int32_t V, int32_t dtype,
-                                       float eps_lo, float eps_hi, float grad_scale,
-                                       float* d_loss, float* d_logp_k, void* d_dH_k, float* d_dW,
-                                       int32_t accumulate_dw, void* d_ws, size_t ws_bytes, void* stream) {
+extern "C" nat_status nat_loss_fwd_bwd_kl(const void* d_hidden_k, const void* d_W, const int32_t* d_ids_k,
+                                          const float* d_old_logp_k, const float* d_adv, const int32_t* d_kept_seq,
+                                          const float* d_kept_w, int32_t N_k, int32_t H, int32_t V, int32_t dtype,
+                                          float eps_lo, float eps_hi, float grad_scale,
+                                          const float* d_ref_logp_k, float beta_kl, int32_t kl_kind,
+                                          float* d_loss, float* d_logp_k, float* d_kl_k, float* d_entropy_k,
+                                          void* d_dH_k, float* d_dW, int32_t accumulate_dw,
+                                          void* d_ws, size_t ws_bytes, void* stream) {
   if (dtype != NAT_DTYPE_F32 && dtype != NAT_DTYPE_BF16) return NAT_UNSUPPORTED_DTYPE;
-  if (N_k < 0 || !(eps_lo >= 0.f) || !(eps_hi >= 0.f)) return NAT_INVALID_ARG;
+  if (N_k < 0 || !(eps_lo >= 0.f) || !(eps_hi >= 0.f) || !(beta_kl >= 0.f)) return NAT_INVALID_ARG;
+  if (kl_kind != NAT_KL_LOG_RATIO && kl_kind != NAT_KL_NONNEG) return NAT_INVALID_ARG;
   if (H <= 0 || V <= 0) return NAT_BAD_SHAPE;
   if (dtype == NAT_DTYPE_BF16 && (H % 64) != 0) return NAT_BAD_SHAPE;
   if (!d_W || !d_loss || !d_dW) return NAT_INVALID_ARG;
   if (N_k > 0 && (!d_hidden_k || !d_ids_k || !d_old_logp_k || !d_adv || !d_kept_seq || !d_kept_w || !d_dH_k))
     return NAT_INVALID_ARG;
+  if (N_k > 0 && beta_kl != 0.f && !d_ref_logp_k) return NAT_INVALID_ARG;
   hipStream_t s = (hipStream_t)stream;
   if (N_k == 0) {
     nat_status st = fill_zero_f32(d_loss, 1, s);
@@ -142,6 +146,18 @@ extern "C" nat_status nat_loss_fwd_bwd(const void* d_hidden_k, const void* d_W, 
   }
   if (!d_ws || ws_bytes < nat_loss_workspace_min_bytes(N_k, H, V, dtype)) return NAT_WORKSPACE_TOO_SMALL;
   LossArgs a{d_hidden_k, d_W, d_ids_k, d_old_logp_k, d_adv, d_kept_seq, d_kept_w, N_k, H, V,
-             eps_lo, eps_hi, grad_scale, d_loss, d_logp_k, d_dH_k, d_dW, accumulate_dw, d_ws, ws_bytes, s};
+             eps_lo, eps_hi, grad_scale, d_loss, d_logp_k, d_dH_k, d_dW, accumulate_dw, d_ws, ws_bytes, s,
+             d_ref_logp_k, beta_kl, kl_kind, d_kl_k, d_entropy_k};
   return dtype == NAT_DTYPE_BF16 ? loss_bf16_run(a) : loss_f32_run(a);
+}
+
+extern "C" nat_status nat_loss_fwd_bwd(const void* d_hidden_k, const void* d_W, const int32_t* d_ids_k,
+                                       const float* d_old_logp_k, const float* d_adv, const int32_t* d_kept_seq,
+                                       const float* d_kept_w, int32_t N_k, int32_t H, int32_t V, int32_t dtype,
+                                       float eps_lo, float eps_hi, float grad_scale,
+                                       float* d_loss, float* d_logp_k, void* d_dH_k, float* d_dW,
+                                       int32_t accumulate_dw, void* d_ws, size_t ws_bytes, void* stream) {
+  return nat_loss_fwd_bwd_kl(d_hidden_k, d_W, d_ids_k, d_old_logp_k, d_adv, d_kept_seq, d_kept_w, N_k, H, V, dtype,
+                             eps_lo, eps_hi, grad_scale, nullptr, 0.f, NAT_KL_LOG_RATIO, d_loss, d_logp_k, nullptr,
+                             nullptr, d_dH_k, d_dW, accumulate_dw, d_ws, ws_bytes, stream);
 }

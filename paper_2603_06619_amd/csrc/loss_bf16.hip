@@ -260,6 +260,7 @@ gemm_nt_kernel(GemmArgs g, Epilogue epi) {
 // ------------------------------------------------------------- epilogues ----
 
 // Logits tile: rows = vocabulary (A = W), columns = tokens of the chunk (B = H_chunk).
+template <bool kEntropy>
 struct LogitsEpilogue {
   int V, n_valid;                  // vocabulary size, valid tokens in the chunk
   int64_t ld_part;                 // leading dimension (tokens) of the partial sums
@@ -267,6 +268,7 @@ struct LogitsEpilogue {
   uint16_t* Et;                    // blocked, rows = vocabulary, k = token: E = exp(z - ref)
   uint16_t* Eb;                    // blocked, rows = token, k = vocabulary: the same values
   float* s_part;                   // [Vp/128, ld_part] partial sums of E
+  float* t_part;                   // [Vp/128, ld_part] partial sums of E (z - ref) (entropy), kEntropy only
   float* z_target;                 // [ld_part] exact target logits
   const int32_t* ids;              // target ids of the chunk's tokens
   const float* ref;                // [ld_part] exponent shift per token
@@ -296,18 +298,24 @@ struct LogitsEpilogue {
           z_target[kk] = zt;
         }
       }
-      float s = 0.f;
+      float s = 0.f, t = 0.f;
 #pragma unroll
       for (int mb = 0; mb < 4; ++mb)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-          float e = __expf(fminf(acc[mb][nb][r] - shift, 70.f));
+          const float zc = fminf(acc[mb][nb][r] - shift, 70.f);
+          float e = __expf(zc);
           if (!all_rows_valid && v0 + mb * 32 + 8 * (r >> 2) + 4 * lhi + (r & 3) >= V) e = 0.f;
           s += e;
+          if (kEntropy) t = fmaf(e, zc, t);
           acc[mb][nb][r] = e;
         }
       s += __shfl_xor(s, 32);
       if (lhi == 0) s_part[(int64_t)granule * ld_part + kk] = s;
+      if (kEntropy) {
+        t += __shfl_xor(t, 32);
+        if (lhi == 0) t_part[(int64_t)granule * ld_part + kk] = t;
+      }
     }
 
     // Et (rows = vocabulary, k = token): neighbouring lanes hold neighbouring tokens; an exchange
@@ -439,20 +447,26 @@ target_logit_kernel(const uint16_t* __restrict__ hidden, const uint16_t* __restr
 // to wavefront gi % 4) and the four partial sums are added in wavefront order, so the result
 // does not depend on timing.
 __global__ void __launch_bounds__(256)
-token_stats_kernel(const float* __restrict__ s_part, int n_granules, int64_t ld, const float* __restrict__ ref,
-                   const float* __restrict__ z_target, int n_valid, int chunk_start,
+token_stats_kernel(const float* __restrict__ s_part, const float* __restrict__ t_part, int n_granules, int64_t ld,
+                   const float* __restrict__ ref, const float* __restrict__ z_target, int n_valid, int chunk_start,
                    const float* __restrict__ old_logp, const float* __restrict__ adv,
                    const int32_t* __restrict__ kept_seq, const float* __restrict__ kept_w,
-                   float eps_lo, float eps_hi, float grad_scale,
+                   float eps_lo, float eps_hi, float grad_scale, KlArgs klp,
                    float* __restrict__ beta_out, float* __restrict__ patch_out,
-                   float* __restrict__ logp_out, float* __restrict__ term) {
+                   float* __restrict__ logp_out, float* __restrict__ kl_out, float* __restrict__ entropy_out,
+                   float* __restrict__ term) {
   __shared__ float s_s[4][64];
+  __shared__ float t_s[4][64];
   const int t = threadIdx.x & 63, part = threadIdx.x >> 6;
   const int kk = blockIdx.x * 64 + t;
-  float s = 0.f;
-  if (kk < n_valid)
+  float s = 0.f, tz = 0.f;
+  if (kk < n_valid) {
     for (int gi = part; gi < n_granules; gi += 4) s += s_part[(int64_t)gi * ld + kk];
+    if (t_part)
+      for (int gi = part; gi < n_granules; gi += 4) tz += t_part[(int64_t)gi * ld + kk];
+  }
   s_s[part][t] = s;
+  t_s[part][t] = tz;
   __syncthreads();
   if (part != 0 || kk >= n_valid) return;
   const float S = (s_s[0][t] + s_s[1][t]) + (s_s[2][t] + s_s[3][t]);
@@ -460,11 +474,15 @@ token_stats_kernel(const float* __restrict__ s_part, int n_granules, int64_t ld,
   const float logp = z_target[kk] - lse;
   const int k = chunk_start + kk;
   const float w = kept_w[k];
-  const TokenScalars ts = grpo_token_scalars(logp, old_logp[k], adv[kept_seq[k]], w, eps_lo, eps_hi, grad_scale);
+  const TokenScalars ts = grpo_token_scalars(logp, old_logp[k], adv[kept_seq[k]], w, eps_lo, eps_hi, grad_scale,
+                                             klp.beta, klp.kind, klp.beta != 0.f ? klp.ref_logp[k] : 0.f);
   beta_out[kk] = -ts.c / S;                            // dz_kv = beta_k E_kv off the target
   patch_out[kk] = -S * (1.f - __expf(logp));           // E'_target with beta_k E' = c_k (1 - p_target)
   if (logp_out) logp_out[k] = logp;
-  term[k] = w * ts.S;
+  if (kl_out) kl_out[k] = ts.kl;
+  // -sum_v p_v log p_v with p_v = E_v / S and log p_v = (z_v - ref) - log S
+  if (entropy_out) entropy_out[k] = logf(S) - ((t_s[0][t] + t_s[1][t]) + (t_s[2][t] + t_s[3][t])) / S;
+  term[k] = w * ts.L;
 }
 
 // Overwrite the target entry of every valid token in both copies of E (see token_stats_kernel).
@@ -484,7 +502,7 @@ static inline int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * 
 
 struct Bf16Plan {
   int64_t Vp, Hp; int n_granules; int cap;      // padded vocabulary / hidden size, granules, chunk capacity (tokens)
-  size_t off_Wb, off_Wtb, off_Hb, off_Hktb, off_Et, off_Eb, off_s, off_zt, off_ref, off_beta, off_patch, off_term, total;
+  size_t off_Wb, off_Wtb, off_Hb, off_Hktb, off_Et, off_Eb, off_s, off_t, off_zt, off_ref, off_beta, off_patch, off_term, total;
 };
 
 static Bf16Plan make_plan(int32_t N_k, int32_t H, int32_t V, int cap) {
@@ -502,6 +520,7 @@ static Bf16Plan make_plan(int32_t N_k, int32_t H, int32_t V, int cap) {
   p.off_Et = take((size_t)p.Vp * cap * 2);      // E: rows = vocabulary, k = tokens
   p.off_Eb = take((size_t)cap * p.Vp * 2);      // E: rows = tokens, k = vocabulary
   p.off_s = take((size_t)p.n_granules * cap * 4);
+  p.off_t = take((size_t)p.n_granules * cap * 4);
   p.off_zt = take((size_t)cap * 4);
   p.off_ref = take((size_t)cap * 4);
   p.off_beta = take((size_t)cap * 4);
@@ -543,6 +562,7 @@ nat_status loss_bf16_run(const LossArgs& a) {
   uint16_t* Et = (uint16_t*)(ws + p.off_Et);
   uint16_t* Eb = (uint16_t*)(ws + p.off_Eb);
   float* s_part = (float*)(ws + p.off_s);
+  float* t_part = a.entropy_out ? (float*)(ws + p.off_t) : nullptr;
   float* zt = (float*)(ws + p.off_zt);
   float* ref = (float*)(ws + p.off_ref);
   float* beta = (float*)(ws + p.off_beta);
@@ -571,15 +591,22 @@ nat_status loss_bf16_run(const LossArgs& a) {
     }
     {  // logits: rows = vocabulary, columns = tokens, contraction over the hidden size
       GemmArgs g{Wb, Hb, H, Vp / kBM, np / kBN};
-      LogitsEpilogue e{V, nv, cap, np / 32, Vp / 32, Et, Eb, s_part, zt, a.ids + c0, ref};
-      nat_status st = launch_gemm(g, e, PC_LOGITS, s);
+      nat_status st;
+      if (t_part) {
+        LogitsEpilogue<true> e{V, nv, cap, np / 32, Vp / 32, Et, Eb, s_part, t_part, zt, a.ids + c0, ref};
+        st = launch_gemm(g, e, PC_LOGITS, s);
+      } else {
+        LogitsEpilogue<false> e{V, nv, cap, np / 32, Vp / 32, Et, Eb, s_part, nullptr, zt, a.ids + c0, ref};
+        st = launch_gemm(g, e, PC_LOGITS, s);
+      }
       if (st != NAT_OK) return st;
     }
     {
       ProfScope prof(PC_TOKEN_STATS, s);
-      token_stats_kernel<<<(nv + 63) / 64, 256, 0, s>>>(s_part, p.n_granules, cap, ref, zt, nv, c0, a.old_logp, a.adv,
-                                                       a.kept_seq, a.kept_w, a.eps_lo, a.eps_hi, a.grad_scale,
-                                                       beta, patch, a.logp, term);
+      token_stats_kernel<<<(nv + 63) / 64, 256, 0, s>>>(s_part, t_part, p.n_granules, cap, ref, zt, nv, c0, a.old_logp,
+                                                       a.adv, a.kept_seq, a.kept_w, a.eps_lo, a.eps_hi, a.grad_scale,
+                                                       KlArgs{a.ref_logp, a.beta_kl, a.kl_kind}, beta, patch, a.logp,
+                                                       a.kl_out, a.entropy_out, term);
       NAT_LAUNCH_CHECK();
       patch_target_kernel<<<(nv + 255) / 256, 256, 0, s>>>(Et, np / 32, Eb, Vp / 32, a.ids + c0, patch, nv);
       NAT_LAUNCH_CHECK();

@@ -25,8 +25,9 @@ __global__ void __launch_bounds__(kF32Threads)
 f32_forward_kernel(const float* __restrict__ hidden, const float* __restrict__ W, const int32_t* __restrict__ ids,
                    const float* __restrict__ old_logp, const float* __restrict__ adv,
                    const int32_t* __restrict__ kept_seq, const float* __restrict__ kept_w,
-                   int chunk_start, int H, int V, float eps_lo, float eps_hi, float grad_scale,
-                   float* __restrict__ dz /*[chunk, V]*/, float* __restrict__ logp_out, float* __restrict__ term) {
+                   int chunk_start, int H, int V, float eps_lo, float eps_hi, float grad_scale, KlArgs klp,
+                   float* __restrict__ dz /*[chunk, V]*/, float* __restrict__ logp_out, float* __restrict__ term,
+                   float* __restrict__ kl_out, float* __restrict__ entropy_out) {
   extern __shared__ float h_s[];             // H floats
   __shared__ float red[4];
   __shared__ float bcast[2];
@@ -51,18 +52,29 @@ f32_forward_kernel(const float* __restrict__ hidden, const float* __restrict__ W
   __syncthreads();
   m = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
   __syncthreads();
-  float s = 0.f;
-  for (int v = threadIdx.x; v < V; v += kF32Threads) s += expf(z[v] - m);
+  float s = 0.f, t = 0.f;                    // sum of e^(z-m) and of e^(z-m) (z-m)
+  for (int v = threadIdx.x; v < V; v += kF32Threads) {
+    const float zc = z[v] - m, e = expf(zc);
+    s += e;
+    t = fmaf(e, zc, t);
+  }
   s = wave_sum_f(s);
-  if (lane == 0) red[wave] = s;
+  t = wave_sum_f(t);
+  __shared__ float red_t[4];
+  if (lane == 0) { red[wave] = s; red_t[wave] = t; }
   __syncthreads();
   if (threadIdx.x == 0) {
-    const float lse = m + logf((red[0] + red[1]) + (red[2] + red[3]));
+    const float sum = (red[0] + red[1]) + (red[2] + red[3]);
+    const float lse = m + logf(sum);
     const float logp = z[ids[k]] - lse;
     const float w = kept_w[k];
-    const TokenScalars ts = grpo_token_scalars(logp, old_logp[k], adv[kept_seq[k]], w, eps_lo, eps_hi, grad_scale);
+    const TokenScalars ts = grpo_token_scalars(logp, old_logp[k], adv[kept_seq[k]], w, eps_lo, eps_hi, grad_scale,
+                                               klp.beta, klp.kind, klp.beta != 0.f ? klp.ref_logp[k] : 0.f);
     if (logp_out) logp_out[k] = logp;
-    term[k] = w * ts.S;
+    if (kl_out) kl_out[k] = ts.kl;
+    // -sum p log p = log(sum) - (sum of e (z - m)) / sum
+    if (entropy_out) entropy_out[k] = logf(sum) - ((red_t[0] + red_t[1]) + (red_t[2] + red_t[3])) / sum;
+    term[k] = w * ts.L;
     bcast[0] = lse;
     bcast[1] = ts.c;
   }
@@ -128,7 +140,8 @@ nat_status loss_f32_run(const LossArgs& a) {
       const int n = a.N_k - c0 < rows ? a.N_k - c0 : rows;
       f32_forward_kernel<<<n, kF32Threads, (size_t)a.H * sizeof(float), s>>>(
           (const float*)a.hidden, (const float*)a.W, a.ids, a.old_logp, a.adv, a.kept_seq, a.kept_w, c0, a.H, a.V,
-          a.eps_lo, a.eps_hi, a.grad_scale, dz, a.logp, term);
+          a.eps_lo, a.eps_hi, a.grad_scale, KlArgs{a.ref_logp, a.beta_kl, a.kl_kind}, dz, a.logp, term,
+          a.kl_out, a.entropy_out);
       NAT_LAUNCH_CHECK();
       f32_dh_kernel<<<n, kF32Threads, 0, s>>>(dz, (const float*)a.W, c0, a.H, a.V, (float*)a.dH);
       NAT_LAUNCH_CHECK();

@@ -66,6 +66,8 @@ struct LossArgs {
   float eps_lo, eps_hi, grad_scale;
   float* loss; float* logp; void* dH; float* dW; int32_t accumulate_dw;
   void* ws; size_t ws_bytes; hipStream_t stream;
+  // KL term of Eq. 4 and the diagnostics of nat_loss_fwd_bwd_kl (all optional)
+  const float* ref_logp; float beta_kl; int32_t kl_kind; float* kl_out; float* entropy_out;
 };
 size_t loss_bf16_workspace_bytes(int32_t N_k, int32_t H, int32_t V, bool minimal);
 nat_status loss_bf16_run(const LossArgs& a);

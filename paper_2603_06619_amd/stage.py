@@ -86,7 +86,8 @@ class LossStage:
         return out
 
     def loss(self, hidden_k, W, ids_k, old_logp_k, adv, kept_seq, kept_w, N_k, eps_lo=0.2, eps_hi=0.2,
-             grad_scale=1.0, dW=None, accumulate_dw=False, ws_bytes=None, want_logp=True):
+             grad_scale=1.0, dW=None, accumulate_dw=False, ws_bytes=None, want_logp=True,
+             ref_logp_k=None, beta_kl=0.0, kl_kind=nb.KL_LOG_RATIO, want_kl=False, want_entropy=False):
         dev = self.device
         V, H = W.shape
         dt = nb.DTYPE_BF16 if W.dtype == torch.bfloat16 else nb.DTYPE_F32
@@ -97,6 +98,14 @@ class LossStage:
                    logp=torch.empty(max(N_k, 1), dtype=torch.float32, device=dev) if want_logp else None,
                    dH=torch.empty((max(N_k, 1), H), dtype=W.dtype, device=dev),
                    dW=dW if dW is not None else torch.empty((V, H), dtype=torch.float32, device=dev))
-        nb.nat_loss_fwd_bwd(hidden_k, W, ids_k, old_logp_k, adv, kept_seq, kept_w, N_k, eps_lo, eps_hi, grad_scale,
-                            out["loss"], out["logp"], out["dH"], out["dW"], accumulate_dw, ws)
+        if ref_logp_k is None and not want_kl and not want_entropy:
+            nb.nat_loss_fwd_bwd(hidden_k, W, ids_k, old_logp_k, adv, kept_seq, kept_w, N_k, eps_lo, eps_hi, grad_scale,
+                                out["loss"], out["logp"], out["dH"], out["dW"], accumulate_dw, ws)
+            return out
+        f32 = lambda: torch.empty(max(N_k, 1), dtype=torch.float32, device=dev)
+        out["kl"] = f32() if want_kl else None
+        out["entropy"] = f32() if want_entropy else None
+        nb.nat_loss_fwd_bwd_kl(hidden_k, W, ids_k, old_logp_k, adv, kept_seq, kept_w, N_k, eps_lo, eps_hi, grad_scale,
+                               ref_logp_k, beta_kl, kl_kind, out["loss"], out["logp"], out["kl"], out["entropy"],
+                               out["dH"], out["dW"], accumulate_dw, ws)
         return out

@@ -60,9 +60,9 @@ def assert_select_compact_equal(h, o, N):
     assert np.array_equal(h["kept_w"].cpu().numpy()[:nk].view(np.uint32), o["kept_w"].view(np.uint32))
 
 
-def oracle_loss(hidden, W, ids, old_logp, adv, kept_seq, kept_w, eps_lo=0.2, eps_hi=0.2, grad_scale=1.0):
+def oracle_loss(hidden, W, ids, old_logp, adv, kept_seq, kept_w, eps_lo=0.2, eps_hi=0.2, grad_scale=1.0, **kl):
     return ogrpo.loss_and_grads(hidden, W, ids, old_logp, np.asarray(adv, np.float64)[kept_seq],
-                                np.asarray(kept_w, np.float64), eps_lo, eps_hi, grad_scale)
+                                np.asarray(kept_w, np.float64), eps_lo, eps_hi, grad_scale, **kl)
 
 
 def make_loss_case(seed, n_tok, H, V, dtype, n_seq=4, noise=0.05, w_std=0.02):

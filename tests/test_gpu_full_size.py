@@ -124,3 +124,39 @@ def test_run_to_run_determinism_at_full_size(full_run):
     assert torch.equal(again["dW"], out["dW"])
     assert torch.equal(again["dH"][:nk], out["dH"][:nk])
     assert torch.equal(again["loss"], out["loss"]) and torch.equal(again["logp"][:nk], out["logp"][:nk])
+
+
+def test_sampled_tokens_with_kl_term_and_entropy_at_full_size(full_run):
+    # same batch and selection through nat_loss_fwd_bwd_kl (Eq. 4 with the non-negative sampled-token
+    # KL form, entropy accumulated in the sweep): sampled kept tokens against the oracle
+    from paper_2603_06619_amd.stage import LossStage
+    b, sc = full_run["batch"], full_run["sc"]
+    nk = sc["n_kept"]
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(5)
+    ref_lp = sc["old_logp_k"] + 0.1 * torch.randn(sc["old_logp_k"].shape, generator=gen, device=DEV)
+    out = LossStage(DEV).loss(sc["hidden_k"], b["W"], sc["ids_k"], sc["old_logp_k"], full_run["adv"], sc["kept_seq"],
+                              sc["kept_w"], nk, ref_logp_k=ref_lp, beta_kl=0.04, kl_kind=ogrpo.KL_NONNEG,
+                              want_kl=True, want_entropy=True)
+    torch.cuda.synchronize()
+    sample = np.unique(np.concatenate([[0, 255, 256, nk - 1, 32767, 32768], np.random.default_rng(1).integers(0, nk, 14)]))
+    sample = sample[sample < nk]
+    sidx = torch.from_numpy(sample).to(DEV)
+    adv = full_run["adv"].cpu().numpy().astype(np.float64)
+    ref = ogrpo.loss_and_grads(sc["hidden_k"][sidx].float().cpu().numpy(), b["W"].float().cpu().numpy(),
+                               sc["ids_k"][sidx].cpu().numpy(), sc["old_logp_k"][sidx].cpu().numpy(),
+                               adv[sc["kept_seq"][sidx].cpu().numpy()], sc["kept_w"][sidx].cpu().numpy().astype(np.float64),
+                               ref_logp=ref_lp[sidx].cpu().numpy(), beta_kl=0.04, kl_kind=ogrpo.KL_NONNEG)
+    assert np.abs(out["logp"][sidx].cpu().numpy() - ref["logp"]).max() < 5e-3
+    ent = out["entropy"][sidx].cpu().numpy()
+    assert np.abs(ent - ref["entropy"]).max() <= 1e-4 * np.abs(ref["entropy"]).max()
+    assert np.abs(out["kl"][sidx].cpu().numpy() - ref["kl"]).max() <= 1e-4 * np.abs(ref["kl"]).max() + 2e-6
+    dH = out["dH"][sidx].float().cpu().numpy()
+    for j in range(len(sample)):
+        den = np.abs(ref["dH"][j]).max()
+        if den > 0:
+            assert np.abs(dH[j] - ref["dH"][j]).max() <= TOL_BF16 * den, (int(sample[j]), den)
+    # near-uniform head: entropies sit just below ln V
+    assert 11.0 < float(out["entropy"][:nk].min()) and float(out["entropy"][:nk].max()) < np.log(b["V"])
+    # the plain entry point on the same inputs gives the same log-probs bit for bit
+    assert torch.equal(out["logp"][:nk], full_run["out"]["logp"][:nk])

@@ -138,6 +138,21 @@ def test_loss_argument_errors(lib):
     assert call(ws=None) == 3
 
 
+def test_loss_kl_argument_errors(lib):
+    fake = ctypes.c_void_p(256)
+    f = ctypes.c_float
+    def call(beta=0.1, kind=0, ref=fake, dtype=1, ws_bytes=1 << 34, N_k=10):
+        return lib.nat_loss_fwd_bwd_kl(fake, fake, fake, fake, fake, fake, fake, N_k, 64, 512, dtype, f(0.2), f(0.2),
+                                       f(1.0), ref, f(beta), kind, fake, None, None, None, fake, fake, 0, fake,
+                                       ws_bytes, None)
+    assert call(beta=-0.5) == 1
+    assert call(beta=float("nan")) == 1
+    assert call(kind=2) == 1 and call(kind=-1) == 1
+    assert call(ref=None) == 1                     # a positive beta needs the reference log-probs
+    assert call(dtype=9) == 4
+    assert call(ws_bytes=64) == 3
+
+
 def test_profile_interface(lib):
     n = lib.nat_profile_num_classes()
     names = [lib.nat_profile_class_name(i) for i in range(n)]

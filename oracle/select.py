@@ -117,11 +117,18 @@ def ht_weight(scheme, T, t, n_rollouts, p=1.0, C=1):
 
 
 def select(cu_seqlens, scheme, p=1.0, C=1, beta=1.0, seed=0, step=0,
-           rollout_id_base=0, scheme_per_rollout=None):
+           rollout_id_base=0, scheme_per_rollout=None, drop_zero_adv=None):
     """Draw the mask for a packed batch.
 
     Returns dict(mask [N] bool, pi [N] fp64, cut_len [B] int32) where cut_len
     is L_i (RPC), K_i (DET) or T_i (FULL, URS).
+
+    drop_zero_adv: optional [B] advantages (Eq. 2).  A rollout whose advantage
+    is exactly 0 has S_{i,t} = 0 and zero gradient at every token (Eq. 3 with
+    A = 0), so when the token loss has no KL term it can be left out without
+    changing the estimate: its mask is cleared and its cut_len set to 0.  The
+    inclusion probabilities (and so the weights of the other rollouts) stay as
+    they are.
     """
     cu = np.asarray(cu_seqlens, dtype=np.int64)
     B = len(cu) - 1
@@ -151,6 +158,9 @@ def select(cu_seqlens, scheme, p=1.0, C=1, beta=1.0, seed=0, step=0,
             cut[i] = K
         else:
             raise ValueError("unknown scheme")
+        if drop_zero_adv is not None and float(drop_zero_adv[i]) == 0.0:
+            mask[sl] = False
+            cut[i] = 0
     return dict(mask=mask, pi=pi, cut_len=cut)
 
 

@@ -21,8 +21,13 @@ WORKLOADS = {
     "qwen3_8b_long_cot": dict(P=8, G=16, H=4096, V=151936, dtype="bf16", lengths=("uniform", 4096, 16384)),
     "wide_head_stress": dict(P=32, G=8, H=5120, V=151936, dtype="bf16",
                              lengths=("pareto", 1.5, 128, 32768), equal_reward_frac=0.1),
+    # the paper's second model (App. C.3): Qwen2.5-Math-7B head, responses up to 3000 tokens, run with
+    # minimum-cutoff RPC (C = 100); a quarter of the prompts get all-equal rewards (zero-advantage groups)
+    "qwen2p5_math_7b_head": dict(P=16, G=8, H=3584, V=152064, dtype="bf16",
+                                 lengths=("lognormal", 900, 0.6, 1, 3000), equal_reward_frac=0.25),
 }
-WORKLOAD_ORDER = ["tiny_fp32", "qwen3_0p6b_head", "qwen3_8b_head_rpc", "qwen3_8b_long_cot", "wide_head_stress"]
+WORKLOAD_ORDER = ["tiny_fp32", "qwen3_0p6b_head", "qwen3_8b_head_rpc", "qwen3_8b_long_cot", "wide_head_stress",
+                  "qwen2p5_math_7b_head"]
 
 W_STD = 0.02
 LOGP_NOISE_STD = 0.05

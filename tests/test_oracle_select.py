@@ -245,3 +245,40 @@ def test_full_scheme_and_empty_batch():
     assert c["kept_idx"].tolist() == list(range(9)) and c["cu_kept"].tolist() == [0, 4, 4, 9]
     d0 = sel.select([0, 0], sel.URS, p=0.5)
     assert d0["mask"].size == 0
+
+
+# ------------------------------------------------- zero-advantage rollouts ----
+
+def test_dropping_zero_advantage_rollouts_leaves_the_estimate_unchanged():
+    # Eq. 3 with A = 0: S = 0 and dS/dlogp = 0 at every token of the rollout, whatever the ratio
+    from oracle import drivers, grpo
+    from test_oracle_grpo import tiny_batch
+    b = tiny_batch(51, [5, 4, 6, 3])
+    b["adv"] = np.array([0.7, 0.0, -1.2, 0.0])
+    cu = b["cu_seqlens"]
+    for scheme, kw in ((sel.FULL, {}), (sel.URS, dict(p=0.5)), (sel.RPC, dict(C=2))):
+        keep_all = sel.select(cu, scheme, seed=4, **kw)
+        dropped = sel.select(cu, scheme, seed=4, drop_zero_adv=b["adv"], **kw)
+        assert not dropped["mask"][cu[1]:cu[2]].any() and not dropped["mask"][cu[3]:cu[4]].any()
+        assert dropped["cut_len"][1] == 0 and dropped["cut_len"][3] == 0
+        for i in (0, 2):                                       # the other rollouts draw exactly as before
+            assert np.array_equal(dropped["mask"][cu[i]:cu[i + 1]], keep_all["mask"][cu[i]:cu[i + 1]])
+        assert np.array_equal(dropped["pi"], keep_all["pi"])
+        e1 = drivers.estimate(b, keep_all["mask"], keep_all["pi"])
+        e2 = drivers.estimate(b, dropped["mask"], dropped["pi"])
+        assert e1["loss"] == e2["loss"] or abs(e1["loss"] - e2["loss"]) < 1e-15
+        assert np.abs(e1["dW"] - e2["dW"]).max() < 1e-15 and np.abs(e1["dH"] - e2["dH"]).max() < 1e-15
+    # with a KL term the dropped tokens would have contributed: the shortcut is exact only for beta_KL = 0
+    bk = dict(b, ref_logp=b["old_logp"] + 0.3, beta_kl=0.5, kl_kind=grpo.KL_NONNEG)
+    e1 = drivers.estimate(bk, keep_all["mask"], keep_all["pi"])
+    e2 = drivers.estimate(bk, dropped["mask"], dropped["pi"])
+    assert abs(e1["loss"] - e2["loss"]) > 1e-4
+
+
+def test_equal_rewards_give_exactly_zero_advantage_and_the_group_is_dropped():
+    from oracle import grpo
+    A = grpo.advantages(np.array([[1.0, 1.0, 1.0, 1.0], [0.0, 1.0, 0.0, 1.0], [0.0, 0.0, 0.0, 0.0]])).reshape(-1)
+    assert (A[:4] == 0).all() and (A[8:] == 0).all() and (A[4:8] != 0).all()
+    cu = np.arange(13) * 10
+    d = sel.select(cu, sel.FULL, drop_zero_adv=A)
+    assert d["mask"].sum() == 40 and d["mask"][40:80].all()

@@ -55,7 +55,10 @@ def parse_args():
                     help="rpc | urs | full | det | schedule | poisson | mixed (even prompts URS, odd prompts Det.Trunc. 50%%); "
                          "default: the workload's own")
     ap.add_argument("--p", type=float, default=0.5)
-    ap.add_argument("--min-cut", type=int, default=1)
+    ap.add_argument("--min-cut", type=int, default=None, help="RPC minimum cutoff C (default 1; 100 for the "
+                                                              "Qwen2.5-Math-7B head workload, as in the paper)")
+    ap.add_argument("--drop-zero-adv", action="store_true",
+                    help="rollouts with advantage exactly 0 keep nothing (exact when the loss has no KL term)")
     ap.add_argument("--seed", type=int, default=2000)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--kl-beta", type=float, default=0.0,
@@ -80,7 +83,10 @@ def cpu_baseline(batch, old_logp, scheme_code, args, torch):
     max_rollouts, max_len = 8, 256
     cu_full = batch["cu_seqlens"]
     rows, lens = [], []
-    for i in range(min(max_rollouts, batch["B"])):
+    # the equal-reward prompts come first in the batch: with --drop-zero-adv sample the last rollouts instead
+    n_s = min(max_rollouts, batch["B"])
+    chosen = list(range(batch["B"] - n_s, batch["B"])) if args.drop_zero_adv else list(range(n_s))
+    for i in chosen:
         T = int(min(max_len, cu_full[i + 1] - cu_full[i]))
         rows.append(np.arange(cu_full[i], cu_full[i] + T))
         lens.append(T)
@@ -93,18 +99,19 @@ def cpu_baseline(batch, old_logp, scheme_code, args, torch):
     W = batch["W"].float().cpu().numpy()
     R = batch["rewards"]
     t0 = time.perf_counter()
-    adv = ogrpo.advantages(R).reshape(-1)[:len(lens)]
+    adv = ogrpo.advantages(R).reshape(-1)[chosen]
     spr = None
     if args.scheme_name == "mixed":
-        spr = np.array([osel.URS if (i // batch["G"]) % 2 == 0 else osel.DET for i in range(len(lens))])
-    d = osel.select(cu, scheme_code, p=args.p, C=args.min_cut, beta=0.5, seed=args.seed, step=0, scheme_per_rollout=spr)
+        spr = np.array([osel.URS if (i // batch["G"]) % 2 == 0 else osel.DET for i in chosen])
+    d = osel.select(cu, scheme_code, p=args.p, C=args.min_cut, beta=0.5, seed=args.seed, step=0, scheme_per_rollout=spr,
+                    drop_zero_adv=adv if args.drop_zero_adv else None)
     c = osel.compact(d["mask"], cu, len(lens), scheme_code, p=args.p, C=args.min_cut, scheme_per_rollout=spr)
     k = c["kept_idx"]
     out = ogrpo.loss_and_grads(hidden[k], W, ids[k], old[k], adv[c["kept_seq"]], c["kept_w"].astype(np.float64))
     dt = time.perf_counter() - t0
     threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
     return dict(value=c["n_kept"] / dt, unit="kept tokens/s", cores=int(threads), kind="oracle",
-                sample=f"first {len(lens)} rollouts truncated to <= {max_len} tokens ({int(cu[-1])} tokens, "
+                sample=f"{'last' if args.drop_zero_adv else 'first'} {len(lens)} rollouts truncated to <= {max_len} tokens ({int(cu[-1])} tokens, "
                        f"{c['n_kept']} kept) at the full head shape, fp64 numpy, {dt:.1f} s",
                 loss=out["loss"])
 
@@ -205,7 +212,9 @@ def main():
     stage = LossStage(dev)
 
     default_scheme = {"qwen3_8b_head_rpc": "rpc", "qwen3_0p6b_head": "urs", "qwen3_8b_long_cot": "urs",
-                      "wide_head_stress": "mixed", "tiny_fp32": "urs"}[args.workload]
+                      "wide_head_stress": "mixed", "tiny_fp32": "urs", "qwen2p5_math_7b_head": "rpc"}[args.workload]
+    if args.min_cut is None:
+        args.min_cut = 100 if args.workload == "qwen2p5_math_7b_head" else 1
     scheme_name = args.scheme or default_scheme
     scheme_code = dict(full=nat.FULL, urs=nat.URS, rpc=nat.RPC, det=nat.DET, mixed=nat.URS,
                        schedule=nat.FULL, poisson=nat.FULL)[scheme_name]
@@ -238,6 +247,7 @@ def main():
     def step(step_no):
         params.step = step_no
         adv = stage.advantage(rewards, P, G)
+        params.drop_zero_adv = adv if args.drop_zero_adv else None
         sc = stage.select_compact(params, cu, B, N, hidden=batch["hidden"], ids=batch["ids"], old_logp=old_logp,
                                   schedule_weights=sched_w, poisson_pi=poisson_pi)
         if args.prefix_pack:
@@ -301,7 +311,8 @@ def main():
         "config": {"workload": args.workload, "P": P, "G": G, "H": H, "V": V, "tokens": N,
                    "kept_tokens_per_step": kept_total / args.steps, "scheme": scheme_name,
                    "p": args.p if scheme_name == "urs" else None, "min_cut": args.min_cut if scheme_name == "rpc" else None,
-                   "kl_beta": args.kl_beta, "entropy": bool(args.entropy)},
+                   "kl_beta": args.kl_beta, "entropy": bool(args.entropy),
+                   "drop_zero_adv": bool(args.drop_zero_adv)},
         "mfma_util_pct_useful_6VH": 100.0 * useful_tflops / PEAK_BF16_TFLOPS,
         "mfma_util_pct_gemm_kernels_only": (100.0 * 6.0 * V * H * kept_total / (gemm_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS
                                             if gemm_ms > 0 else None),

@@ -70,6 +70,8 @@ const char* nat_status_string(nat_status s);
  *   change with batching or sharding.
  *   d_scheme_per_rollout: optional DEVICE array [B] overriding `scheme` per
  *   rollout (mixed batches); NULL = uniform scheme.
+ *   d_drop_zero_adv: see the field; honoured by nat_select, nat_select_schedule and
+ *   nat_select_poisson (inclusion probabilities and weights of the other rollouts do not change).
  */
 typedef struct nat_select_params {
   int32_t scheme;
@@ -80,6 +82,10 @@ typedef struct nat_select_params {
   uint32_t step;
   int32_t rollout_id_base;   /* global id of rollout 0 of this batch */
   const int32_t* d_scheme_per_rollout;
+  const float* d_drop_zero_adv;   /* optional DEVICE array [B] of advantages (Eq. 2): rollouts whose advantage
+                                     is exactly 0 keep nothing (cut_len 0).  With A = 0, Eq. 3 gives S = 0 and a
+                                     zero gradient at every token, so the estimate is unchanged as long as the
+                                     token loss has no KL term; NULL = keep the paper's behaviour */
 } nat_select_params;
 
 /*

@@ -22,17 +22,19 @@ class NatError(RuntimeError):
 class _CSelectParams(ctypes.Structure):
     _fields_ = [("scheme", ctypes.c_int32), ("min_cut", ctypes.c_int32), ("p", ctypes.c_double),
                 ("trunc_frac", ctypes.c_double), ("seed", ctypes.c_uint64), ("step", ctypes.c_uint32),
-                ("rollout_id_base", ctypes.c_int32), ("d_scheme_per_rollout", ctypes.c_void_p)]
+                ("rollout_id_base", ctypes.c_int32), ("d_scheme_per_rollout", ctypes.c_void_p),
+                ("d_drop_zero_adv", ctypes.c_void_p)]
 
 
 class SelectParams:
     """Selection parameters of nat_select / nat_compact (see nat_select_params in nat.h)."""
 
     def __init__(self, scheme, p=1.0, min_cut=1, trunc_frac=1.0, seed=0, step=0, rollout_id_base=0,
-                 scheme_per_rollout=None):
+                 scheme_per_rollout=None, drop_zero_adv=None):
         self.scheme, self.p, self.min_cut, self.trunc_frac = scheme, p, min_cut, trunc_frac
         self.seed, self.step, self.rollout_id_base = seed, step, rollout_id_base
         self.scheme_per_rollout = scheme_per_rollout      # int32 device tensor [B] or None
+        self.drop_zero_adv = drop_zero_adv                # float32 device tensor [B] of advantages or None
 
     def _c(self):
         spr = self.scheme_per_rollout
@@ -40,7 +42,9 @@ class SelectParams:
             _check(spr, torch.int32, "scheme_per_rollout")
         return _CSelectParams(int(self.scheme), int(self.min_cut), float(self.p), float(self.trunc_frac),
                               int(self.seed) & (2 ** 64 - 1), int(self.step) & 0xFFFFFFFF, int(self.rollout_id_base),
-                              spr.data_ptr() if spr is not None else None)
+                              spr.data_ptr() if spr is not None else None,
+                              _check(self.drop_zero_adv, torch.float32, "drop_zero_adv").data_ptr()
+                              if self.drop_zero_adv is not None else None)
 
 
 def library_path():

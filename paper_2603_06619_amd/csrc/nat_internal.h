@@ -30,6 +30,7 @@ struct SelectArgs {
   uint64_t urs_threshold;       // floor(p * 2^32)
   uint32_t key0, key1, step; int32_t rollout_id_base;
   const int32_t* scheme_per_rollout;
+  const float* drop_zero_adv;   // optional [B]: rollouts with advantage exactly 0 keep nothing
 };
 nat_status validate_select(const nat_select_params* p, SelectArgs* out);
 

@@ -37,6 +37,7 @@ __device__ __forceinline__ uint64_t block_scan_u64(uint64_t v, uint64_t* wave_to
 // survival function for every position.
 __global__ void __launch_bounds__(kSchedThreads)
 schedule_cut_kernel(uint32_t key0, uint32_t key1, uint32_t step, int32_t rollout_id_base,
+                    const float* __restrict__ drop_zero_adv,
                     const uint32_t* __restrict__ weights, const int64_t* __restrict__ cu,
                     int32_t* __restrict__ cut_len, double* __restrict__ pi) {
   __shared__ uint64_t wave_tot[kSchedThreads / 64];
@@ -57,11 +58,16 @@ schedule_cut_kernel(uint32_t key0, uint32_t key1, uint32_t step, int32_t rollout
   __syncthreads();
   if (A == 0) {                                   // no schedule: keep the rollout whole, p = 1
     for (int64_t j = threadIdx.x; j < T; j += kSchedThreads) p[j] = 1.0;
-    if (threadIdx.x == 0) cut_len[i] = (int32_t)T;
+    if (threadIdx.x == 0) cut_len[i] = (drop_zero_adv && drop_zero_adv[i] == 0.f) ? 0 : (int32_t)T;
     return;
   }
   const u32x4 rnd = philox4x32_10(u32x4{0u, (uint32_t)(rollout_id_base + i), 2u, step}, key0, key1);
-  const uint64_t r = __umul64hi(((uint64_t)rnd.x << 32) | (uint64_t)rnd.y, A);   // in [0, A)
+  uint64_t r = __umul64hi(((uint64_t)rnd.x << 32) | (uint64_t)rnd.y, A);         // in [0, A)
+  const bool dropped = drop_zero_adv && drop_zero_adv[i] == 0.f;                 // keeps nothing: no position
+  if (dropped) {                                                                 // qualifies below
+    r = ~0ull;
+    if (threadIdx.x == 0) cut_len[i] = 0;
+  }
 
   const double den = (double)A;
   uint64_t carry = 0;                              // running sum of all earlier positions
@@ -92,7 +98,7 @@ schedule_cut_kernel(uint32_t key0, uint32_t key1, uint32_t step, int32_t rollout
 
 __global__ void __launch_bounds__(256)
 poisson_mask_kernel(uint32_t key0, uint32_t key1, uint32_t step, int32_t rollout_id_base,
-                    const double* __restrict__ pi, const int64_t* __restrict__ cu, int B, int64_t N,
+                    const float* __restrict__ drop_zero_adv, const double* __restrict__ pi, const int64_t* __restrict__ cu, int B, int64_t N,
                     uint32_t* __restrict__ mask_bits) {
   const int64_t n = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   bool keep = false;
@@ -105,7 +111,7 @@ poisson_mask_kernel(uint32_t key0, uint32_t key1, uint32_t step, int32_t rollout
     else if (p > 0.0) thr = (uint64_t)floor(p * 4294967296.0);
     const u32x4 r = philox4x32_10(u32x4{(uint32_t)(t0 >> 2), (uint32_t)(rollout_id_base + i), 0u, step}, key0, key1);
     const uint32_t word = (t0 & 3) == 0 ? r.x : (t0 & 3) == 1 ? r.y : (t0 & 3) == 2 ? r.z : r.w;
-    keep = (uint64_t)word < thr;
+    keep = (uint64_t)word < thr && !(drop_zero_adv && drop_zero_adv[i] == 0.f);
   }
   const uint64_t ballot = __ballot(keep);
   if ((threadIdx.x & 63) == 0 && n < N) {
@@ -208,7 +214,7 @@ extern "C" nat_status nat_select_schedule(const nat_select_params* params, const
   ProfScope prof(PC_SCHEDULE, s);
   schedule_cut_kernel<<<(unsigned)B, kSchedThreads, 0, s>>>(
       (uint32_t)(params->seed & 0xFFFFFFFFull), (uint32_t)(params->seed >> 32), params->step,
-      params->rollout_id_base, d_weights, d_cu_seqlens, d_cut_len, d_pi);
+      params->rollout_id_base, params->d_drop_zero_adv, d_weights, d_cu_seqlens, d_cut_len, d_pi);
   NAT_LAUNCH_CHECK();
   return launch_prefix_mask(d_cu_seqlens, B, N, d_cut_len, d_mask_bits, s);
 }
@@ -224,7 +230,7 @@ extern "C" nat_status nat_select_poisson(const nat_select_params* params, const 
   ProfScope prof(PC_SCHEDULE, s);
   poisson_mask_kernel<<<(unsigned)((N + 255) / 256), 256, 0, s>>>(
       (uint32_t)(params->seed & 0xFFFFFFFFull), (uint32_t)(params->seed >> 32), params->step,
-      params->rollout_id_base, d_pi, d_cu_seqlens, B, N, d_mask_bits);
+      params->rollout_id_base, params->d_drop_zero_adv, d_pi, d_cu_seqlens, B, N, d_mask_bits);
   NAT_LAUNCH_CHECK();
   return NAT_OK;
 }

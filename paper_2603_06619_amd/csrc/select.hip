@@ -42,6 +42,7 @@ __global__ void select_cut_kernel(SelectArgs a, const int64_t* __restrict__ cu, 
   } else if (scheme == NAT_SCHEME_DET) {
     cut = (int64_t)floor(a.trunc_frac * (double)T);
   }
+  if (a.drop_zero_adv && a.drop_zero_adv[i] == 0.f) cut = 0;
   cut_len[i] = (int32_t)cut;
 }
 
@@ -64,6 +65,7 @@ select_mask_kernel(SelectArgs a, const int64_t* __restrict__ cu, int B, int64_t 
     } else {
       keep = t0 < (int64_t)cut_len[i];
     }
+    if (a.drop_zero_adv && a.drop_zero_adv[i] == 0.f) keep = false;
   }
   const uint64_t ballot = __ballot(keep);
   // groups past ceil(N/64) have no words in the mask (the last block may hold some)
@@ -90,6 +92,7 @@ nat_status validate_select(const nat_select_params* p, SelectArgs* out) {
   out->step = p->step;
   out->rollout_id_base = p->rollout_id_base;
   out->scheme_per_rollout = p->d_scheme_per_rollout;
+  out->drop_zero_adv = p->d_drop_zero_adv;
   return NAT_OK;
 }
 

@@ -25,10 +25,11 @@ def to_dev(x, dtype=None):
     return t.to(DEV)
 
 
-def oracle_select_compact(cu, scheme, n_rollouts=None, p=1.0, C=1, beta=1.0, seed=0, step=0, base=0, spr=None):
+def oracle_select_compact(cu, scheme, n_rollouts=None, p=1.0, C=1, beta=1.0, seed=0, step=0, base=0, spr=None,
+                          drop=None):
     B = len(cu) - 1
     d = osel.select(cu, scheme, p=p, C=C, beta=beta, seed=seed, step=step, rollout_id_base=base,
-                    scheme_per_rollout=spr)
+                    scheme_per_rollout=spr, drop_zero_adv=drop)
     c = osel.compact(d["mask"], cu, B if n_rollouts is None else n_rollouts, scheme, p=p, C=C,
                      scheme_per_rollout=spr)
     c.update(d)
@@ -36,12 +37,13 @@ def oracle_select_compact(cu, scheme, n_rollouts=None, p=1.0, C=1, beta=1.0, see
 
 
 def hip_select_compact(stage, cu, scheme, n_rollouts=None, p=1.0, C=1, beta=1.0, seed=0, step=0, base=0, spr=None,
-                       hidden=None, ids=None, old_logp=None):
+                       hidden=None, ids=None, old_logp=None, drop=None):
     import paper_2603_06619_amd as nat
     B = len(cu) - 1
     N = int(cu[-1])
     params = nat.SelectParams(scheme, p=p, min_cut=C, trunc_frac=beta, seed=seed, step=step, rollout_id_base=base,
-                              scheme_per_rollout=to_dev(np.asarray(spr, dtype=np.int32)) if spr is not None else None)
+                              scheme_per_rollout=to_dev(np.asarray(spr, dtype=np.int32)) if spr is not None else None,
+                              drop_zero_adv=to_dev(np.asarray(drop, dtype=np.float32)) if drop is not None else None)
     out = stage.select_compact(params, to_dev(np.asarray(cu, dtype=np.int64)), B, N, n_rollouts, hidden, ids, old_logp)
     return out
 

@@ -106,3 +106,21 @@ def test_advantage_matches_eq2(stage):
         ref = ogrpo.advantages(R, 1e-6)
         assert np.abs(adv - ref).max() <= 2e-6 * max(1.0, np.abs(ref).max())
         assert (adv[np.ptp(R, axis=1) == 0] == 0).all()       # equal rewards: exactly zero
+
+
+@pytest.mark.parametrize("scheme,kw", [(osel.FULL, {}), (osel.URS, dict(p=0.5)), (osel.RPC, dict(C=100)),
+                                        (osel.DET, dict(beta=0.5))])
+def test_zero_advantage_rollouts_are_dropped(stage, scheme, kw):
+    # the paper's second model workload: a quarter of the prompts have all-equal rewards; Eq. 2 on the device
+    # gives exactly 0 there, and those rollouts keep nothing
+    lay = si.batch_layout("qwen2p5_math_7b_head", 5000)
+    cu, B, P, G = lay["cu_seqlens"], lay["B"], lay["P"], lay["G"]
+    adv_dev = stage.advantage(to_dev(lay["rewards"].reshape(-1)), P, G)
+    adv = adv_dev.cpu().numpy()
+    adv_ref = ogrpo.advantages(lay["rewards"]).reshape(-1)
+    assert np.array_equal(adv == 0, adv_ref == 0) and (adv == 0).sum() >= B // 4
+    o = oracle_select_compact(cu, scheme, seed=3, step=2, drop=adv_ref, **kw)
+    h = hip_select_compact(stage, cu, scheme, seed=3, step=2, drop=adv, **kw)
+    assert_select_compact_equal(h, o, lay["N"])
+    full = oracle_select_compact(cu, scheme, seed=3, step=2, **kw)
+    assert o["n_kept"] < full["n_kept"]

@@ -35,7 +35,7 @@ def test_equal_reward_groups_and_workload_table():
     rng = np.random.default_rng(2)
     R = si.draw_rewards(32, 8, rng, 0.1)
     assert all(len(set(R[i])) == 1 for i in range(4))
-    assert [si.WORKLOADS[n]["H"] for n in si.WORKLOAD_ORDER] == [64, 1024, 4096, 4096, 5120]
+    assert [si.WORKLOADS[n]["H"] for n in si.WORKLOAD_ORDER] == [64, 1024, 4096, 4096, 5120, 3584]
     assert si.WORKLOADS["qwen3_8b_head_rpc"]["V"] == 151936
 
 

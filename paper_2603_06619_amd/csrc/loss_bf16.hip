@@ -33,12 +33,23 @@ namespace nat {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
-constexpr int kBM = 256, kBN = 256, kBK = 32;     // block tile; 4 wavefronts of 128 x 128
+constexpr int kBM = 256, kBN = 256, kBK = 32;     // block tile: 4 wavefronts of 128 x 128 or 8 of 128 x 64
 constexpr int kStages = 4;                        // LDS ring of k-slices (4 x 32 KiB)
-constexpr int kThreads = 256;
 constexpr int kGranule = 128;                     // vocabulary rows per soft-max partial
 constexpr int kTileBytes = kBM * kBK * 2;         // 16 KiB per operand per stage
-constexpr int kLoadsPerWave = 2 * (kTileBytes / 1024) / 4;   // direct-to-LDS loads per wavefront per stage (A and B)
+// Wavefronts per workgroup of each contraction (4: one per SIMD, 128 x 128 each, 256 accumulator
+// registers; 8: two per SIMD, 128 x 64 each, so one can issue MFMAs while the other waits).
+// Measured on the Qwen3-8B head: the dW contraction is 3 % faster with 8, dH 2 % slower, the
+// logits contraction unchanged.
+#ifndef NAT_WAVES_LOGITS
+#define NAT_WAVES_LOGITS 4
+#endif
+#ifndef NAT_WAVES_DHIDDEN
+#define NAT_WAVES_DHIDDEN 4
+#endif
+#ifndef NAT_WAVES_DWEIGHT
+#define NAT_WAVES_DWEIGHT 8
+#endif
 constexpr int kMaxChunk = 32768;                  // token rows per chunk (recommended workspace)
 
 __device__ __forceinline__ uint16_t f32_to_bf16_bits(float x) {
@@ -120,11 +131,13 @@ __device__ __forceinline__ void tile_of_block(const GemmArgs& g, int& tm, int& t
 __device__ __forceinline__ int lds_chunk_off(int r, int c) { return r * (kBK * 2) + ((c ^ ((r >> 2) & 3)) << 4); }
 
 // Global -> LDS copy of one [256][32] bf16 operand block (16 KiB, contiguous in memory)
-// without staging registers: each wavefront issues 4 direct-to-LDS loads of 16 bytes per
-// lane.  One instruction copies 1 KiB (16 tile rows) linearly: the hardware places lane l at
-// byte 16*l of that KiB, and the block in memory already has the LDS tile's chunk order.
+// without staging registers: the NW wavefronts issue 16 direct-to-LDS loads of 16 bytes per
+// lane between them.  One instruction copies 1 KiB (16 tile rows) linearly: the hardware
+// places lane l at byte 16*l of that KiB, and the block in memory already has the LDS tile's
+// chunk order.
+template <int NW>
 struct TileLoader {
-  static constexpr int kLoads = kTileBytes / 1024 / 4;      // per wavefront
+  static constexpr int kLoads = kTileBytes / 1024 / NW;     // per wavefront
   const uint16_t* src;           // this lane's chunk in k-slice 0 of load 0
 
   __device__ __forceinline__ void init(const uint16_t* base, int tile, int kb, int wave, int lane) {
@@ -135,66 +148,73 @@ struct TileLoader {
 #pragma unroll
     for (int j = 0; j < kLoads; ++j) {
       __builtin_amdgcn_global_load_lds(
-          (const __attribute__((address_space(1))) void*)(p + j * 64 * kBK),
-          (__attribute__((address_space(3))) void*)(lds_tile + (j * 4 + wave) * 1024), 16, 0, 0);
+          (const __attribute__((address_space(1))) void*)(p + j * NW * 16 * kBK),
+          (__attribute__((address_space(3))) void*)(lds_tile + (j * NW + wave) * 1024), 16, 0, 0);
     }
   }
 };
 
-__device__ __forceinline__ void load_frags(const char* a_s, const char* b_s, int wm, int wn, int l32, int lhi, int ks,
-                                           bf16x8 (&af)[4], bf16x8 (&bfr)[4]) {
+// fragments of k-substep ks: four 32-row blocks of A from row a_row0, NB 32-row blocks of B from b_row0
+template <int NB>
+__device__ __forceinline__ void load_frags(const char* a_s, const char* b_s, int a_row0, int b_row0, int l32, int lhi,
+                                           int ks, bf16x8 (&af)[4], bf16x8 (&bfr)[NB]) {
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    af[i] = *(const bf16x8*)(a_s + lds_chunk_off(wm * 128 + i * 32 + l32, ks * 2 + lhi));
-    bfr[i] = *(const bf16x8*)(b_s + lds_chunk_off(wn * 128 + i * 32 + l32, ks * 2 + lhi));
-  }
+  for (int i = 0; i < 4; ++i) af[i] = *(const bf16x8*)(a_s + lds_chunk_off(a_row0 + i * 32 + l32, ks * 2 + lhi));
+#pragma unroll
+  for (int j = 0; j < NB; ++j) bfr[j] = *(const bf16x8*)(b_s + lds_chunk_off(b_row0 + j * 32 + l32, ks * 2 + lhi));
 }
 
-// 8 of the 16 MFMAs of one k-substep: A fragments i0, i0+1 against all four B fragments
-__device__ __forceinline__ void mfma_half(f32x16 (&acc)[4][4], const bf16x8 (&af)[4], const bf16x8 (&bfr)[4], int i0) {
+template <int NB>
+__device__ __forceinline__ void mfma_substep(f32x16 (&acc)[4][NB], const bf16x8 (&af)[4], const bf16x8 (&bfr)[NB]) {
 #pragma unroll
-  for (int i = i0; i < i0 + 2; ++i)
+  for (int i = 0; i < 4; ++i)
 #pragma unroll
-    for (int j = 0; j < 4; ++j)
+    for (int j = 0; j < NB; ++j)
       acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
 }
 
 // s_waitcnt immediates (gfx9 encoding: vmcnt in bits 3:0 and 15:14, expcnt 6:4, lgkmcnt 11:8)
 constexpr int waitcnt_vm(int n) { return (n & 15) | ((n >> 4) << 14) | 0x0f70; }
 
-// acc[mb][nb] element r of lane l is C[wm*128 + mb*32 + 8*(r/4) + 4*(l/32) + r%4][wn*128 + nb*32 + l%32]
-template <class Epilogue>
-__global__ void __launch_bounds__(kThreads, 1)
+// NW wavefronts in a 2 x (NW/2) grid over the 256 x 256 tile: wavefront (wm, wn) owns rows
+// wm*128.. and columns wn*(NB*32).. with NB = 16/NW (4 wavefronts: 128 columns, 8: 64 columns).
+// acc[mb][nb] element r of lane l is C[row0 + mb*32 + 8*(r/4) + 4*(l/32) + r%4][col0 + nb*32 + l%32]
+template <class Epilogue, int NW>
+__global__ void __launch_bounds__(NW * 64, 1)
 gemm_nt_kernel(GemmArgs g, Epilogue epi) {
+  constexpr int NB = 16 / NW;                                  // 32-column blocks per wavefront
+  constexpr int kLoadsPerWave = 2 * (kTileBytes / 1024) / NW;  // direct-to-LDS loads per wavefront per slice
+  constexpr int kMfma = 4 * NB, kFragReads = 4 + NB;           // per k-substep
   __shared__ __attribute__((aligned(1024))) char lds[kStages][2][kTileBytes];
   int tm, tn;
   tile_of_block(g, tm, tn);
   const int m0 = tm * kBM, n0 = tn * kBN;
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int wm = wave >> 1, wn = wave & 1;
+  const int wm = wave / (NW / 2), wn = wave % (NW / 2);
+  const int a_row0 = wm * 128, b_row0 = wn * (NB * 32);
   const int l32 = lane & 31, lhi = lane >> 5;
 
-  f32x16 acc[4][4];
+  f32x16 acc[4][NB];
 #pragma unroll
   for (int i = 0; i < 4; ++i)
 #pragma unroll
-    for (int j = 0; j < 4; ++j)
+    for (int j = 0; j < NB; ++j)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-  TileLoader la, lb;
+  TileLoader<NW> la, lb;
   const int kt_n = g.K / kBK;
   la.init(g.A, tm, kt_n, wave, lane);
   lb.init(g.B, tn, kt_n, wave, lane);
 
   // Software pipeline over k-slices of 32.  Slice kt lives in lds[kt % 4]; three slices are
-  // in flight while one is consumed, so a load has three iterations (96 MFMAs per wavefront)
-  // to land.  Loads complete in issue order, hence "slice kt+1 has landed" is vmcnt(16): the
-  // two younger slices (8 loads each per wavefront) may still be outstanding.  The barrier
-  // sits before the second half of the slice's MFMAs, so the refill of the released buffer
-  // and the first fragment reads of the next slice issue under those 16 MFMAs.  Slices past
-  // the end re-load the last one (harmless) to keep the body branch-free and the count fixed.
+  // in flight while one is consumed, so a load has three iterations to land.  Loads complete
+  // in issue order, hence "slice kt+1 has landed" is vmcnt(2 * kLoadsPerWave): the two younger
+  // slices may still be outstanding.  The barrier sits before the second half of the slice's
+  // MFMAs, so the refill of the released buffer and the first fragment reads of the next slice
+  // issue under those MFMAs.  Slices past the end re-load the last one (harmless) to keep the
+  // body branch-free and the count fixed.
 #pragma unroll
   for (int st = 0; st < kStages; ++st) {
     const int k = st < kt_n ? st : kt_n - 1;
@@ -203,27 +223,26 @@ gemm_nt_kernel(GemmArgs g, Epilogue epi) {
   }
   __builtin_amdgcn_s_waitcnt(waitcnt_vm((kStages - 1) * kLoadsPerWave));
   __syncthreads();
-  bf16x8 af[2][4], bfr[2][4];
-  load_frags(lds[0][0], lds[0][1], wm, wn, l32, lhi, 0, af[0], bfr[0]);
+  bf16x8 af[2][4], bfr[2][NB];
+  load_frags<NB>(lds[0][0], lds[0][1], a_row0, b_row0, l32, lhi, 0, af[0], bfr[0]);
 
   for (int kt = 0; kt < kt_n; ++kt) {
     const int cur = kt % kStages, nxt = (kt + 1) % kStages;
-    // first k-substep of slice kt; the second substep's fragments are read under its first 8 MFMAs
-    load_frags(lds[cur][0], lds[cur][1], wm, wn, l32, lhi, 1, af[1], bfr[1]);
-    mfma_half(acc, af[0], bfr[0], 0);
-    mfma_half(acc, af[0], bfr[0], 2);
+    // first k-substep of slice kt; the second substep's fragments are read under its first MFMAs
+    load_frags<NB>(lds[cur][0], lds[cur][1], a_row0, b_row0, l32, lhi, 1, af[1], bfr[1]);
+    mfma_substep<NB>(acc, af[0], bfr[0]);
 #pragma unroll
-    for (int x = 0; x < 8; ++x) {
+    for (int x = 0; x < kFragReads; ++x) {
       __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);     // 1 MFMA
       __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);     // 1 LDS read
     }
-    __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
-    // keep all 16 MFMAs of the first substep on this side of the barrier (their fragment
+    __builtin_amdgcn_sched_group_barrier(0x008, kMfma - kFragReads, 0);
+    // keep all MFMAs of the first substep on this side of the barrier (their fragment
     // registers are overwritten right after it)
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
-      for (int j = 0; j < 4; ++j) asm volatile("" : "+a"(acc[i][j]));
+      for (int j = 0; j < NB; ++j) asm volatile("" : "+a"(acc[i][j]));
     __builtin_amdgcn_sched_barrier(0);
     // slice kt+1 has landed (this wavefront's share; the barrier covers the others) and this
     // wavefront has finished reading slice kt, whose buffer is refilled below
@@ -231,9 +250,8 @@ gemm_nt_kernel(GemmArgs g, Epilogue epi) {
     __builtin_amdgcn_s_barrier();
     __builtin_amdgcn_sched_barrier(0);
     // second k-substep; under it: first fragments of slice kt+1, then the refill of lds[cur]
-    load_frags(lds[nxt][0], lds[nxt][1], wm, wn, l32, lhi, 0, af[0], bfr[0]);
-    mfma_half(acc, af[1], bfr[1], 0);
-    mfma_half(acc, af[1], bfr[1], 2);
+    load_frags<NB>(lds[nxt][0], lds[nxt][1], a_row0, b_row0, l32, lhi, 0, af[0], bfr[0]);
+    mfma_substep<NB>(acc, af[1], bfr[1]);
     {
       int k2 = kt + kStages;
       k2 = k2 < kt_n ? k2 : kt_n - 1;
@@ -241,20 +259,28 @@ gemm_nt_kernel(GemmArgs g, Epilogue epi) {
       lb.issue(lds[cur][1], k2, wave);
     }
 #pragma unroll
-    for (int x = 0; x < 8; ++x) {
+    for (int x = 0; x < kFragReads; ++x) {
       __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);     // 1 MFMA
       __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);     // 1 LDS read
     }
+    if (NW == 4) {
 #pragma unroll
-    for (int x = 0; x < 8; ++x) {
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);     // 1 MFMA
-      __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);     // 1 global->LDS load
+      for (int x = 0; x < 8; ++x) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // 1 MFMA
+        __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);   // 1 global->LDS load
+      }
+    } else {
+#pragma unroll
+      for (int x = 0; x < 2; ++x) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // 1 MFMA
+        __builtin_amdgcn_sched_group_barrier(0x020, 2, 0);   // 2 global->LDS loads
+      }
     }
   }
   __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));   // no direct-to-LDS load may outlive the block
   __syncthreads();
 
-  epi(acc, m0 + wm * 128, n0 + wn * 128, lane, wave, &lds[0][0][0]);
+  epi(acc, m0 + a_row0, n0 + b_row0, lane, wave, &lds[0][0][0]);
 }
 
 // ------------------------------------------------------------- epilogues ----
@@ -275,12 +301,14 @@ struct LogitsEpilogue {
 
   static constexpr int kStageRow = 144;        // bytes per token row of the LDS staging tile (64 bf16 + pad)
 
-  __device__ __forceinline__ void operator()(f32x16 (&acc)[4][4], int v0, int k0, int lane, int wave, char* lds) const {
+  template <int NB>
+  __device__ __forceinline__ void operator()(f32x16 (&acc)[4][NB], int v0, int k0, int lane, int wave, char* lds) const {
+    constexpr int kTok = NB * 32;                          // token columns of this wavefront
     const int l32 = lane & 31, lhi = lane >> 5;
     const int granule = v0 / kGranule;
     const bool all_rows_valid = v0 + kGranule <= V;
 #pragma unroll
-    for (int nb = 0; nb < 4; ++nb) {
+    for (int nb = 0; nb < NB; ++nb) {
       const int kk = k0 + nb * 32 + l32;                 // token column (always inside the padded chunk)
       const bool tok_valid = kk < n_valid;
       const int y = tok_valid ? ids[kk] : -1;
@@ -322,7 +350,7 @@ struct LogitsEpilogue {
     // with lane^1 lets even lanes store rows r (two tokens, 4 bytes) and odd lanes rows r+1.
     const bool odd = lane & 1;
 #pragma unroll
-    for (int nb = 0; nb < 4; ++nb) {
+    for (int nb = 0; nb < NB; ++nb) {
       const int kk_pair = k0 + nb * 32 + (l32 & ~1);
 #pragma unroll
       for (int mb = 0; mb < 4; ++mb)
@@ -340,13 +368,13 @@ struct LogitsEpilogue {
 
     // Eb (rows = token, k = vocabulary): each lane holds 4 consecutive vocabulary entries of its
     // token; stage 64 vocabulary rows at a time through LDS (free after the k-loop) so that the
-    // global stores are 16 bytes per lane and contiguous (128 tokens x 64 bytes per k-slice).
-    char* stage = lds + wave * (128 * kStageRow);
+    // global stores are 16 bytes per lane and contiguous (kTok tokens x 64 bytes per k-slice).
+    char* stage = lds + wave * (kTok * kStageRow);
 #pragma unroll
     for (int half = 0; half < 2; ++half) {
       __syncthreads();
 #pragma unroll
-      for (int nb = 0; nb < 4; ++nb)
+      for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
         for (int mbh = 0; mbh < 2; ++mbh)
 #pragma unroll
@@ -359,9 +387,9 @@ struct LogitsEpilogue {
           }
       __syncthreads();
 #pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        const int q = i * 64 + lane;                    // slice q/512, token (q%512)/4, 16-byte chunk q%4
-        const int sl = q >> 9, tok = (q & 511) >> 2, ch = q & 3;
+      for (int i = 0; i < kTok / 8; ++i) {
+        const int q = i * 64 + lane;                    // slice q/(4 kTok), token (q%(4 kTok))/4, 16-byte chunk q%4
+        const int sl = q / (4 * kTok), tok = (q % (4 * kTok)) >> 2, ch = q & 3;
         const uint4 val = *(const uint4*)(stage + tok * kStageRow + sl * 64 + ch * 16);
         *(uint4*)(Eb + blk_off(k0 + tok, v0 + half * 64 + sl * 32 + ch * 8, kb_z)) = val;
       }
@@ -375,7 +403,8 @@ struct DHiddenEpilogue {
   uint16_t* dH;                    // rows of this chunk, [n_valid, H] bf16
   const float* beta;               // [n_valid]
 
-  __device__ __forceinline__ void operator()(f32x16 (&acc)[4][4], int k0, int h0, int lane, int, char*) const {
+  template <int NB>
+  __device__ __forceinline__ void operator()(f32x16 (&acc)[4][NB], int k0, int h0, int lane, int, char*) const {
     const int l32 = lane & 31, lhi = lane >> 5;
 #pragma unroll
     for (int mb = 0; mb < 4; ++mb)
@@ -385,7 +414,7 @@ struct DHiddenEpilogue {
         if (k >= n_valid) continue;
         const float b = beta[k];
 #pragma unroll
-        for (int nb = 0; nb < 4; ++nb) {
+        for (int nb = 0; nb < NB; ++nb) {
           const int h = h0 + nb * 32 + l32;
           if (h < H) dH[(int64_t)k * H + h] = f32_to_bf16_bits(b * acc[mb][nb][r]);
         }
@@ -398,10 +427,11 @@ struct DWeightEpilogue {
   int V, H, accumulate;
   float* dW;                       // [V, H] fp32
 
-  __device__ __forceinline__ void operator()(f32x16 (&acc)[4][4], int v0, int h0, int lane, int, char*) const {
+  template <int NB>
+  __device__ __forceinline__ void operator()(f32x16 (&acc)[4][NB], int v0, int h0, int lane, int, char*) const {
     const int l32 = lane & 31, lhi = lane >> 5;
 #pragma unroll
-    for (int nb = 0; nb < 4; ++nb) {
+    for (int nb = 0; nb < NB; ++nb) {
       const int h = h0 + nb * 32 + l32;
       if (h >= H) continue;
 #pragma unroll
@@ -539,10 +569,10 @@ size_t loss_bf16_workspace_bytes(int32_t N_k, int32_t H, int32_t V, bool minimal
   return make_plan(N_k, H, V, minimal ? kBN : recommended_cap(N_k)).total;
 }
 
-template <class Epi>
+template <int NW, class Epi>
 static nat_status launch_gemm(const GemmArgs& g, const Epi& epi, int prof_class, hipStream_t s) {
   ProfScope prof(prof_class, s);
-  gemm_nt_kernel<Epi><<<g.tiles_m * g.tiles_n, kThreads, 0, s>>>(g, epi);
+  gemm_nt_kernel<Epi, NW><<<g.tiles_m * g.tiles_n, NW * 64, 0, s>>>(g, epi);
   NAT_LAUNCH_CHECK();
   return NAT_OK;
 }
@@ -594,10 +624,10 @@ nat_status loss_bf16_run(const LossArgs& a) {
       nat_status st;
       if (t_part) {
         LogitsEpilogue<true> e{V, nv, cap, np / 32, Vp / 32, Et, Eb, s_part, t_part, zt, a.ids + c0, ref};
-        st = launch_gemm(g, e, PC_LOGITS, s);
+        st = launch_gemm<NAT_WAVES_LOGITS>(g, e, PC_LOGITS, s);
       } else {
         LogitsEpilogue<false> e{V, nv, cap, np / 32, Vp / 32, Et, Eb, s_part, nullptr, zt, a.ids + c0, ref};
-        st = launch_gemm(g, e, PC_LOGITS, s);
+        st = launch_gemm<NAT_WAVES_LOGITS>(g, e, PC_LOGITS, s);
       }
       if (st != NAT_OK) return st;
     }
@@ -619,13 +649,13 @@ nat_status loss_bf16_run(const LossArgs& a) {
     {  // dH: rows = tokens, columns = hidden units, contraction over the padded vocabulary
       GemmArgs g{Eb, Wtb, Vp, np / kBM, Hp / kBN};
       DHiddenEpilogue e{nv, H, (uint16_t*)a.dH + (int64_t)c0 * H, beta};
-      nat_status st = launch_gemm(g, e, PC_DHIDDEN, s);
+      nat_status st = launch_gemm<NAT_WAVES_DHIDDEN>(g, e, PC_DHIDDEN, s);
       if (st != NAT_OK) return st;
     }
     {  // dW: rows = vocabulary, columns = hidden units, contraction over the chunk's (padded) tokens
       GemmArgs g{Et, Hktb, np, Vp / kBM, Hp / kBN};
       DWeightEpilogue e{V, H, (c0 > 0 || a.accumulate_dw) ? 1 : 0, a.dW};
-      nat_status st = launch_gemm(g, e, PC_DWEIGHT, s);
+      nat_status st = launch_gemm<NAT_WAVES_DWEIGHT>(g, e, PC_DWEIGHT, s);
       if (st != NAT_OK) return st;
     }
   }

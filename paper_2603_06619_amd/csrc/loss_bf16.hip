@@ -203,6 +203,10 @@ gemm_nt_kernel(GemmArgs g, Epilogue epi) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
+  // per-column scalars the epilogue needs (token id, exponent shift): fetched now, used after the k-loop
+  typename Epilogue::template Pre<NB> pre;
+  epi.prefetch(pre, n0 + b_row0, lane);
+
   TileLoader<NW> la, lb;
   const int kt_n = g.K / kBK;
   la.init(g.A, tm, kt_n, wave, lane);
@@ -280,7 +284,7 @@ gemm_nt_kernel(GemmArgs g, Epilogue epi) {
   __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));   // no direct-to-LDS load may outlive the block
   __syncthreads();
 
-  epi(acc, m0 + a_row0, n0 + b_row0, lane, wave, &lds[0][0][0]);
+  epi(acc, pre, m0 + a_row0, n0 + b_row0, lane, wave, &lds[0][0][0]);
 }
 
 // ------------------------------------------------------------- epilogues ----
@@ -301,8 +305,21 @@ struct LogitsEpilogue {
 
   static constexpr int kStageRow = 144;        // bytes per token row of the LDS staging tile (64 bf16 + pad)
 
+  template <int NB> struct Pre { int y[NB]; float shift[NB]; };
   template <int NB>
-  __device__ __forceinline__ void operator()(f32x16 (&acc)[4][NB], int v0, int k0, int lane, int wave, char* lds) const {
+  __device__ __forceinline__ void prefetch(Pre<NB>& pre, int k0, int lane) const {
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) {
+      const int kk = k0 + nb * 32 + (lane & 31);
+      const bool tok_valid = kk < n_valid;
+      pre.y[nb] = tok_valid ? ids[kk] : -1;
+      pre.shift[nb] = tok_valid ? ref[kk] : 0.f;
+    }
+  }
+
+  template <int NB>
+  __device__ __forceinline__ void operator()(f32x16 (&acc)[4][NB], const Pre<NB>& pre, int v0, int k0, int lane, int wave,
+                                             char* lds) const {
     constexpr int kTok = NB * 32;                          // token columns of this wavefront
     const int l32 = lane & 31, lhi = lane >> 5;
     const int granule = v0 / kGranule;
@@ -310,9 +327,8 @@ struct LogitsEpilogue {
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) {
       const int kk = k0 + nb * 32 + l32;                 // token column (always inside the padded chunk)
-      const bool tok_valid = kk < n_valid;
-      const int y = tok_valid ? ids[kk] : -1;
-      const float shift = tok_valid ? ref[kk] : 0.f;
+      const int y = pre.y[nb];
+      const float shift = pre.shift[nb];
       // exact target logit, if the target row lies in this granule and in this lane's half
       const int yrel = y - v0;
       if (__any(yrel >= 0 && yrel < kGranule)) {
@@ -326,21 +342,37 @@ struct LogitsEpilogue {
           z_target[kk] = zt;
         }
       }
-      float s = 0.f, t = 0.f;
+      // E = exp(min(z - shift, 70)) as 2^(min(z * log2(e) - shift * log2(e), 70 * log2(e))): one fma, one
+      // min and the hardware exponential per logit.  Sixteen logits at a time with independent
+      // temporaries and four running sums, so that the dependent-instruction latency of a lone
+      // wavefront per SIMD is overlapped; only the last vocabulary tile pays for the row check.
+      constexpr float kLog2e = 1.44269504088896340736f, kLn2 = 0.69314718055994530942f;
+      const float nshift2 = -shift * kLog2e;
+      float s4[4] = {0.f, 0.f, 0.f, 0.f}, t4[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-      for (int mb = 0; mb < 4; ++mb)
+      for (int mb = 0; mb < 4; ++mb) {
+        float x2[16], e[16];
+#pragma unroll
+        for (int r = 0; r < 16; ++r) x2[r] = fminf(fmaf(acc[mb][nb][r], kLog2e, nshift2), 70.f * kLog2e);
+#pragma unroll
+        for (int r = 0; r < 16; ++r) e[r] = __builtin_amdgcn_exp2f(x2[r]);
+        if (!all_rows_valid) {
+#pragma unroll
+          for (int r = 0; r < 16; ++r)
+            if (v0 + mb * 32 + 8 * (r >> 2) + 4 * lhi + (r & 3) >= V) e[r] = 0.f;
+        }
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-          const float zc = fminf(acc[mb][nb][r] - shift, 70.f);
-          float e = __expf(zc);
-          if (!all_rows_valid && v0 + mb * 32 + 8 * (r >> 2) + 4 * lhi + (r & 3) >= V) e = 0.f;
-          s += e;
-          if (kEntropy) t = fmaf(e, zc, t);
-          acc[mb][nb][r] = e;
+          s4[r & 3] += e[r];
+          if (kEntropy) t4[r & 3] = fmaf(e[r], x2[r], t4[r & 3]);
+          acc[mb][nb][r] = e[r];
         }
+      }
+      float s = (s4[0] + s4[1]) + (s4[2] + s4[3]);
       s += __shfl_xor(s, 32);
       if (lhi == 0) s_part[(int64_t)granule * ld_part + kk] = s;
       if (kEntropy) {
+        float t = ((t4[0] + t4[1]) + (t4[2] + t4[3])) * kLn2;     // back to natural-log units
         t += __shfl_xor(t, 32);
         if (lhi == 0) t_part[(int64_t)granule * ld_part + kk] = t;
       }
@@ -403,8 +435,11 @@ struct DHiddenEpilogue {
   uint16_t* dH;                    // rows of this chunk, [n_valid, H] bf16
   const float* beta;               // [n_valid]
 
+  template <int NB> struct Pre {};
+  template <int NB> __device__ __forceinline__ void prefetch(Pre<NB>&, int, int) const {}
   template <int NB>
-  __device__ __forceinline__ void operator()(f32x16 (&acc)[4][NB], int k0, int h0, int lane, int, char*) const {
+  __device__ __forceinline__ void operator()(f32x16 (&acc)[4][NB], const Pre<NB>&, int k0, int h0, int lane, int,
+                                             char*) const {
     const int l32 = lane & 31, lhi = lane >> 5;
 #pragma unroll
     for (int mb = 0; mb < 4; ++mb)
@@ -427,8 +462,11 @@ struct DWeightEpilogue {
   int V, H, accumulate;
   float* dW;                       // [V, H] fp32
 
+  template <int NB> struct Pre {};
+  template <int NB> __device__ __forceinline__ void prefetch(Pre<NB>&, int, int) const {}
   template <int NB>
-  __device__ __forceinline__ void operator()(f32x16 (&acc)[4][NB], int v0, int h0, int lane, int, char*) const {
+  __device__ __forceinline__ void operator()(f32x16 (&acc)[4][NB], const Pre<NB>&, int v0, int h0, int lane, int,
+                                             char*) const {
     const int l32 = lane & 31, lhi = lane >> 5;
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) {

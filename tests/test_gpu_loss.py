@@ -149,3 +149,21 @@ def test_bf16_qwen3_8b_head_reduced_batch(stage):
     out = hip_loss(stage, case, "bf16")
     errs = check(out, ref, 130, TOL_BF16)
     print("qwen3-8B head reduced batch: rel err logp/dH/dW =", errs)
+
+
+@pytest.mark.parametrize("H,V,label", [(5120, 151936, "wide head"), (3584, 152064, "Qwen2.5-Math-7B head")])
+def test_bf16_other_full_head_shapes_reduced_batch(stage, H, V, label):
+    # the remaining head shapes of the workloads: hidden sizes that are 20 and 14 tiles of 256 wide
+    case = make_loss_case(23 + H, 150, H, V, "bf16")
+    ref = oracle_loss(**case)
+    out = hip_loss(stage, case, "bf16")
+    errs = check(out, ref, 150, TOL_BF16)
+    print(label, "reduced batch: rel err logp/dH/dW =", errs)
+
+
+def test_bf16_hidden_size_not_a_multiple_of_the_tile(stage):
+    # H = 320 (a multiple of 64 but not of 256): the last hidden tile is ragged in dH and dW
+    case = make_loss_case(77, 300, 320, 1500, "bf16", noise=0.1, w_std=0.1)
+    ref = oracle_loss(**case)
+    out = hip_loss(stage, case, "bf16")
+    check(out, ref, 300, TOL_BF16)

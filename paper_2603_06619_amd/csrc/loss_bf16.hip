@@ -41,6 +41,17 @@ constexpr int kTileBytes = kBM * kBK * 2;         // 16 KiB per operand per stag
 // registers; 8: two per SIMD, 128 x 64 each, so one can issue MFMAs while the other waits).
 // Measured on the Qwen3-8B head: the dW contraction is 3 % faster with 8, dH 2 % slower, the
 // logits contraction unchanged.
+// Tile rows per group of the block -> tile map, per contraction (measured: 4 is 1-2 % faster than 8
+// for the two backward contractions, 2 and 6 are slower, 16 is 8 % slower).
+#ifndef NAT_GROUP_LOGITS
+#define NAT_GROUP_LOGITS 8
+#endif
+#ifndef NAT_GROUP_DHIDDEN
+#define NAT_GROUP_DHIDDEN 4
+#endif
+#ifndef NAT_GROUP_DWEIGHT
+#define NAT_GROUP_DWEIGHT 4
+#endif
 #ifndef NAT_WAVES_LOGITS
 #define NAT_WAVES_LOGITS 4
 #endif
@@ -104,18 +115,19 @@ struct GemmArgs {
   const uint16_t* B;          // [tiles_n * 256, K] in the blocked layout
   int K;                      // multiple of kBK
   int tiles_m, tiles_n;
+  int group_m;                // tile rows walked together (see tile_of_block)
 };
 
 // Block id -> output tile.  Blocks are dealt round-robin to the 8 XCDs, so ids
 // congruent mod 8 share an L2: give each XCD a contiguous range of tiles, walked
-// in groups of 8 tile-rows so that concurrently resident blocks reuse A and B tiles.
+// in groups of `group_m` tile-rows so that concurrently resident blocks reuse A and B tiles.
 __device__ __forceinline__ void tile_of_block(const GemmArgs& g, int& tm, int& tn) {
   const int total = g.tiles_m * g.tiles_n;
   const int pid = blockIdx.x;
   int logical = pid;
   const int per_xcd = total / 8;
   if (pid < per_xcd * 8) logical = (pid & 7) * per_xcd + (pid >> 3);
-  constexpr int kGroupM = 8;
+  const int kGroupM = g.group_m;
   const int group_sz = kGroupM * g.tiles_n;
   const int group = logical / group_sz;
   const int first_m = group * kGroupM;
@@ -658,7 +670,7 @@ nat_status loss_bf16_run(const LossArgs& a) {
       NAT_LAUNCH_CHECK();
     }
     {  // logits: rows = vocabulary, columns = tokens, contraction over the hidden size
-      GemmArgs g{Wb, Hb, H, Vp / kBM, np / kBN};
+      GemmArgs g{Wb, Hb, H, Vp / kBM, np / kBN, NAT_GROUP_LOGITS};
       nat_status st;
       if (t_part) {
         LogitsEpilogue<true> e{V, nv, cap, np / 32, Vp / 32, Et, Eb, s_part, t_part, zt, a.ids + c0, ref};
@@ -685,13 +697,13 @@ nat_status loss_bf16_run(const LossArgs& a) {
       NAT_LAUNCH_CHECK();
     }
     {  // dH: rows = tokens, columns = hidden units, contraction over the padded vocabulary
-      GemmArgs g{Eb, Wtb, Vp, np / kBM, Hp / kBN};
+      GemmArgs g{Eb, Wtb, Vp, np / kBM, Hp / kBN, NAT_GROUP_DHIDDEN};
       DHiddenEpilogue e{nv, H, (uint16_t*)a.dH + (int64_t)c0 * H, beta};
       nat_status st = launch_gemm<NAT_WAVES_DHIDDEN>(g, e, PC_DHIDDEN, s);
       if (st != NAT_OK) return st;
     }
     {  // dW: rows = vocabulary, columns = hidden units, contraction over the chunk's (padded) tokens
-      GemmArgs g{Et, Hktb, np, Vp / kBM, Hp / kBN};
+      GemmArgs g{Et, Hktb, np, Vp / kBM, Hp / kBN, NAT_GROUP_DWEIGHT};
       DWeightEpilogue e{V, H, (c0 > 0 || a.accumulate_dw) ? 1 : 0, a.dW};
       nat_status st = launch_gemm<NAT_WAVES_DWEIGHT>(g, e, PC_DWEIGHT, s);
       if (st != NAT_OK) return st;

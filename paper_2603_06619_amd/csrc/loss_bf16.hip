@@ -152,16 +152,25 @@ struct TileLoader {
   static constexpr int kLoads = kTileBytes / 1024 / NW;     // per wavefront
   const uint16_t* src;           // this lane's chunk in k-slice 0 of load 0
 
+  // A wavefront copies kLoads consecutive KiB of the block (16 * kLoads rows): the loads of one
+  // slice differ only in the instruction's immediate offset, which the hardware adds to both the
+  // global and the LDS address, so one address and one LDS base serve all of them.
   __device__ __forceinline__ void init(const uint16_t* base, int tile, int kb, int wave, int lane) {
-    src = base + (int64_t)tile * kb * kBlkElems + wave * (16 * kBK) + lane * 8;
+    src = base + (int64_t)tile * kb * kBlkElems + wave * (kLoads * 16 * kBK) + lane * 8;
   }
   __device__ __forceinline__ void issue(char* lds_tile, int kt, int wave) const {
     const uint16_t* p = src + (int64_t)kt * kBlkElems;
-#pragma unroll
-    for (int j = 0; j < kLoads; ++j) {
-      __builtin_amdgcn_global_load_lds(
-          (const __attribute__((address_space(1))) void*)(p + j * NW * 16 * kBK),
-          (__attribute__((address_space(3))) void*)(lds_tile + (j * NW + wave) * 1024), 16, 0, 0);
+    char* dst = lds_tile + wave * (kLoads * 1024);
+    static_assert(kLoads == 4 || kLoads == 2, "immediate offsets below are written out");
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)p,
+                                     (__attribute__((address_space(3))) void*)dst, 16, 0, 0);
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)p,
+                                     (__attribute__((address_space(3))) void*)dst, 16, 1024, 0);
+    if (kLoads == 4) {
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)p,
+                                       (__attribute__((address_space(3))) void*)dst, 16, 2048, 0);
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)p,
+                                       (__attribute__((address_space(3))) void*)dst, 16, 3072, 0);
     }
   }
 };

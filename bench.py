@@ -25,11 +25,11 @@ GEMM_CLASSES = ("logits_gemm", "dhidden_gemm", "dweight_gemm")
 # what the same counter reads for the library's row-gather copy kernel of known size
 # (factors 1.954 and 0.993; see profiles/).  Valid only for the kernel source they were taken
 # on: bench.py reports null when the source hash differs.
-TRAFFIC_SOURCE_SHA256_16 = "7e0b35302aef0d6f"
+TRAFFIC_SOURCE_SHA256_16 = "6e7554bb5a3a9446"
 TRAFFIC_BYTES_PER_LAUNCH = {
-    "logits_gemm": 57707467388 + 17494164098,
-    "dhidden_gemm": 51782278504 + 232602505,
-    "dweight_gemm": 68634932907 + 2607756920,
+    "logits_gemm": 56746093180 + 17899414834,
+    "dhidden_gemm": 63486867387 + 232602505,
+    "dweight_gemm": 64482072793 + 2607756920,
 }
 
 
@@ -194,8 +194,8 @@ def main():
             sys.exit(2)
         return stress_select(args)
     if args.gpus != 1:
-        print(f"bench.py measures one GPU only (got --gpus {args.gpus}); the path shards by rollout, "
-              "see DESIGN.md", file=sys.stderr)
+        print(f"bench.py measures one GPU only (got --gpus {args.gpus}): no multi-GPU path is built; the stage "
+              "shards by rollout (each GPU holds the head, one sum of dW and the loss at the end)", file=sys.stderr)
         sys.exit(2)
     import numpy as np
     import torch

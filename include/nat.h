@@ -132,7 +132,8 @@ size_t nat_compact_workspace_bytes(int64_t N);
  *     d_ids [N] -> d_ids_k [cap],  d_old_logp [N] -> d_old_logp_k [cap];
  *   d_ws / ws_bytes: workspace of at least nat_compact_workspace_bytes(N).
  * Errors: as nat_select, plus n_rollouts_global <= 0, H <= 0 or a row size that is not
- * a multiple of 16 bytes when gathering -> NAT_BAD_SHAPE, workspace too small.
+ * a multiple of 16 bytes when gathering -> NAT_BAD_SHAPE, d_hidden / d_hidden_k not 16-byte
+ * aligned -> NAT_INVALID_ARG, workspace too small.
  */
 nat_status nat_compact(const nat_select_params* params, int32_t n_rollouts_global,
                        const uint32_t* d_mask_bits, const int64_t* d_cu_seqlens, int32_t B, int64_t N,
@@ -257,6 +258,7 @@ size_t nat_loss_workspace_min_bytes(int32_t N_k, int32_t H, int32_t V, int32_t d
  *   workspace.  That shift requires log(p_max / p_target) < 70 for every kept token (larger
  *   numerators are clamped); the fp32 path has no such bound.
  * N_k = 0 is valid: loss = 0, d_dW zeroed unless accumulating, d_dH_k untouched.
+ *   Alignment: d_hidden_k, d_W, d_dH_k, d_dW 16 bytes; d_ws 256 bytes (else NAT_INVALID_ARG).
  * Errors: NULL pointer, N_k < 0, eps < 0 -> NAT_INVALID_ARG; H <= 0, V <= 0, or (bf16) H not
  * a multiple of 64 -> NAT_BAD_SHAPE; dtype unknown -> NAT_UNSUPPORTED_DTYPE; ws_bytes below
  * nat_loss_workspace_min_bytes -> NAT_WORKSPACE_TOO_SMALL.

@@ -145,6 +145,10 @@ extern "C" nat_status nat_loss_fwd_bwd_kl(const void* d_hidden_k, const void* d_
     return accumulate_dw ? NAT_OK : fill_zero_f32(d_dW, (size_t)V * (size_t)H, s);
   }
   if (!d_ws || ws_bytes < nat_loss_workspace_min_bytes(N_k, H, V, dtype)) return NAT_WORKSPACE_TOO_SMALL;
+  // the kernels use 16-byte accesses on the caller's arrays and 256-byte aligned workspace sections
+  if (((uintptr_t)d_ws & 255) || ((uintptr_t)d_hidden_k & 15) || ((uintptr_t)d_W & 15) || ((uintptr_t)d_dH_k & 15) ||
+      ((uintptr_t)d_dW & 15))
+    return NAT_INVALID_ARG;
   LossArgs a{d_hidden_k, d_W, d_ids_k, d_old_logp_k, d_adv, d_kept_seq, d_kept_w, N_k, H, V,
              eps_lo, eps_hi, grad_scale, d_loss, d_logp_k, d_dH_k, d_dW, accumulate_dw, d_ws, ws_bytes, s,
              d_ref_logp_k, beta_kl, kl_kind, d_kl_k, d_entropy_k};

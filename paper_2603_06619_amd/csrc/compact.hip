@@ -193,6 +193,7 @@ nat_status compact_run(const SelectArgs& a, const CompactArgs& c) {
     if (c.H <= 0) return NAT_BAD_SHAPE;
     row_bytes = (int64_t)c.H * (c.dtype == NAT_DTYPE_F32 ? 4 : 2);
     if (row_bytes % 16 != 0) return NAT_BAD_SHAPE;
+    if (((uintptr_t)c.hidden & 15) || ((uintptr_t)c.hidden_k & 15)) return NAT_INVALID_ARG;   // 16-byte row copies
   }
   if (!c.ws || c.ws_bytes < nat_compact_workspace_bytes(c.N)) return NAT_WORKSPACE_TOO_SMALL;
 

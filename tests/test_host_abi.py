@@ -84,6 +84,7 @@ def test_compact_argument_errors(lib):
     assert lib.nat_compact(*args(hidden=fake)) == 1                       # gather pair incomplete
     assert lib.nat_compact(*args(hidden=fake, hidden_k=fake, H=3, dtype=1)) == 2   # row not 16-byte multiple
     assert lib.nat_compact(*args(hidden=fake, hidden_k=fake, H=64, dtype=5)) == 4
+    assert lib.nat_compact(*args(hidden=ctypes.c_void_p(260), hidden_k=fake, H=64, dtype=1)) == 1   # misaligned rows
     assert lib.nat_compact(*args(ws_bytes=8)) == 3
     assert lib.nat_compact(*args(ws=None)) == 3
 
@@ -136,6 +137,9 @@ def test_loss_argument_errors(lib):
     assert call(hidden=None) == 1
     assert call(ws_bytes=1024) == 3
     assert call(ws=None) == 3
+    assert call(ws=ctypes.c_void_p(264)) == 1            # workspace not 256-byte aligned
+    assert call(hidden=ctypes.c_void_p(260)) == 1        # 16-byte accesses on the caller's arrays
+    assert call(W=ctypes.c_void_p(258)) == 1
 
 
 def test_loss_kl_argument_errors(lib):

@@ -14,7 +14,7 @@ bool g_prof_on = false;
 std::vector<EventPair> g_prof_records;
 const char* const kClassNames[PC_NUM] = {
     "advantage", "select", "compact", "gather", "transpose", "logits_gemm", "token_stats",
-    "rescale", "dhidden_gemm", "dweight_gemm", "loss_reduce", "f32_path", "fill", "schedule", "prefix_pack"};
+    "dhidden_gemm", "dweight_gemm", "loss_reduce", "f32_path", "fill", "schedule", "prefix_pack"};
 }  // namespace
 
 ProfScope::ProfScope(int cls, hipStream_t s) : cls_(cls), s_(s), rec_(nullptr) {

@@ -10,7 +10,7 @@ namespace nat {
 // Kernel classes for the optional per-kernel timing.
 enum ProfClass : int {
   PC_ADVANTAGE = 0, PC_SELECT, PC_COMPACT, PC_GATHER, PC_TRANSPOSE, PC_LOGITS, PC_TOKEN_STATS,
-  PC_RESCALE, PC_DHIDDEN, PC_DWEIGHT, PC_LOSS_REDUCE, PC_F32_PATH, PC_FILL, PC_SCHEDULE, PC_PREFIX_PACK, PC_NUM
+  PC_DHIDDEN, PC_DWEIGHT, PC_LOSS_REDUCE, PC_F32_PATH, PC_FILL, PC_SCHEDULE, PC_PREFIX_PACK, PC_NUM
 };
 
 // Brackets the launches issued during its lifetime with two events when timing is on.

@@ -52,6 +52,17 @@ def token_logp(hidden, W, ids):
     return logpi[np.arange(len(ids)), np.asarray(ids, dtype=np.int64)]
 
 
+def forward_logp(hidden, W, ids):
+    """Forward pass alone (the log-probability evaluation that precedes the loss in Sec. 2's cost
+    structure: behaviour and reference log-probs are produced this way).  Returns dict(logp [n],
+    entropy [n])."""
+    Hm = np.asarray(hidden, dtype=np.float64)
+    if Hm.shape[0] == 0:
+        return dict(logp=np.zeros(0), entropy=np.zeros(0))
+    logpi = log_softmax_rows(Hm @ np.asarray(W, dtype=np.float64).T)
+    return dict(logp=logpi[np.arange(Hm.shape[0]), np.asarray(ids, dtype=np.int64)], entropy=entropy_rows(logpi))
+
+
 def surrogate(logp, old_logp, A, eps_lo, eps_hi):
     """Eq. 1 and Eq. 3 for arrays of tokens.
 

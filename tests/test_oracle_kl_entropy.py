@@ -148,3 +148,17 @@ def test_prop1_holds_for_the_token_loss_with_kl(kind):
         assert abs(e["prob"] - 1) < 1e-12
         assert abs(e["loss"] - ft["loss"]) < 1e-12
         assert np.abs(e["dW"] - ft["dW"]).max() < 1e-12 and np.abs(e["dH"] - ft["dH"]).max() < 1e-12
+
+
+# ---------------------------------------------------------------- forward pass alone
+
+def test_forward_logp_is_the_library_log_softmax_and_matches_the_loss_path():
+    b = tiny_batch(12, [6, 5])
+    f = grpo.forward_logp(b["hidden"], b["W"], b["ids"])
+    ref = torch.log_softmax(torch.tensor(b["hidden"]) @ torch.tensor(b["W"]).T, dim=1)
+    assert np.allclose(f["logp"], ref[torch.arange(11), torch.tensor(b["ids"])].numpy(), rtol=1e-13)
+    assert np.allclose(f["entropy"], -(ref.exp() * ref).sum(1).numpy(), rtol=1e-13)
+    out = grpo.loss_and_grads(b["hidden"], b["W"], b["ids"], b["old_logp"], np.ones(11), np.ones(11))
+    assert np.array_equal(out["logp"], f["logp"]) and np.array_equal(out["entropy"], f["entropy"])
+    e = grpo.forward_logp(np.zeros((0, 8)), b["W"], [])
+    assert e["logp"].shape == (0,)

@@ -64,6 +64,8 @@ def parse_args():
     ap.add_argument("--kl-beta", type=float, default=0.0,
                     help="weight of the KL term of the token loss (reference log-probs are synthetic); 0 = off")
     ap.add_argument("--entropy", action="store_true", help="also accumulate the per-token entropy in the sweep")
+    ap.add_argument("--forward-only", action="store_true",
+                    help="time nat_logp_fwd (log-probs of the kept tokens, 2VH flops per token) instead of the loss")
     ap.add_argument("--prefix-pack", action="store_true",
                     help="also build the truncated batch (prompt + kept prefix) each step; prefix schemes only")
     ap.add_argument("--prompts", type=int, default=None, help="override the number of prompts (smaller batch)")
@@ -253,6 +255,8 @@ def main():
         if args.prefix_pack:
             stage.prefix_pack(prompt_len, cu, sc["cut_len"], B, N, rows_cap, 1)
         nk = sc["n_kept"]
+        if args.forward_only:
+            return nk, stage.logp(sc["hidden_k"], batch["W"], sc["ids_k"], nk, want_entropy=args.entropy)
         kl = {}
         if args.kl_beta > 0 or args.entropy:
             # reference log-probs: the behaviour log-probs stand in (only their shape matters for the timing)
@@ -302,7 +306,8 @@ def main():
     kernels = {k: dict(ms_per_step=v[0] / args.steps, launches_per_step=v[1] / args.steps)
                for k, v in prof.items() if v[1] > 0}
     gemm_ms = sum(prof[c][0] for c in GEMM_CLASSES)
-    useful_tflops = 6.0 * V * H * kept_total / wall / 1e12
+    n_gemms = 1.0 if args.forward_only else 3.0                    # contractions per kept token
+    useful_tflops = 2.0 * n_gemms * V * H * kept_total / wall / 1e12
 
     result = {
         "metric": METRIC, "value": value, "unit": "kept tokens/s", "n_gpus": 1, "steps": args.steps,
@@ -312,17 +317,18 @@ def main():
                    "kept_tokens_per_step": kept_total / args.steps, "scheme": scheme_name,
                    "p": args.p if scheme_name == "urs" else None, "min_cut": args.min_cut if scheme_name == "rpc" else None,
                    "kl_beta": args.kl_beta, "entropy": bool(args.entropy),
-                   "drop_zero_adv": bool(args.drop_zero_adv)},
+                   "drop_zero_adv": bool(args.drop_zero_adv),
+                   "forward_only": bool(args.forward_only)},
         "mfma_util_pct_useful_6VH": 100.0 * useful_tflops / PEAK_BF16_TFLOPS,
-        "mfma_util_pct_gemm_kernels_only": (100.0 * 6.0 * V * H * kept_total / (gemm_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS
+        "mfma_util_pct_gemm_kernels_only": (100.0 * 2.0 * n_gemms * V * H * kept_total / (gemm_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS
                                             if gemm_ms > 0 else None),
         "gpu_event_ms_per_step": ms_total / args.steps,
-        "loss": float(out["loss"].item()),
+        "loss": None if args.forward_only else float(out["loss"].item()),
         "peak_hbm_gb": torch.cuda.max_memory_allocated() / 1e9,
         "roofline": roofline,
         "kernels": kernels,
     }
-    if not args.no_cpu_baseline and scheme_name not in ("schedule", "poisson"):
+    if not args.no_cpu_baseline and scheme_name not in ("schedule", "poisson") and not args.forward_only:
         result["cpu_baseline"] = cpu_baseline(batch, old_logp, scheme_code, args, torch)
     print(json.dumps(result))
 

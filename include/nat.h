@@ -229,6 +229,26 @@ nat_status nat_prefix_pack(const int32_t* d_prompt_len, const int64_t* d_cu_seql
                            void* stream);
 
 /*
+ * Forward pass alone: log-probability of given tokens under the head (the evaluation that
+ * produces behaviour and reference log-probs, Sec. 2 "forward pass of the current policy to
+ * compute token log-probabilities"), and optionally the entropy of each row:
+ *     z_k = W h_k,  logp_k = z_k[ids_k] - logsumexp(z_k),  entropy_k = -sum_v p_v log p_v.
+ * Same projection kernel and the same arithmetic as nat_loss_fwd_bwd (identical log-probs for
+ * identical chunking), but no soft-max numerators are written: 2 V H flops per token.
+ *   d_hidden_k [N_k, H], d_W [V, H] row-major (bf16 or f32), d_ids_k [N_k] int32 in [0, V);
+ *   d_logp_k [N_k] float out;  d_entropy_k [N_k] float out or NULL;
+ *   d_ws / ws_bytes: at least nat_logp_workspace_min_bytes (nat_logp_workspace_bytes recommended).
+ * The bf16 path shifts exponents by the target logit: as for nat_loss_fwd_bwd, log(p_max/p_target)
+ * must stay below 70.  N_k = 0 is valid and does nothing.
+ * Errors and alignment: as nat_loss_fwd_bwd.
+ */
+size_t nat_logp_workspace_bytes(int32_t N_k, int32_t H, int32_t V, int32_t dtype);
+size_t nat_logp_workspace_min_bytes(int32_t N_k, int32_t H, int32_t V, int32_t dtype);
+nat_status nat_logp_fwd(const void* d_hidden_k, const void* d_W, const int32_t* d_ids_k,
+                        int32_t N_k, int32_t H, int32_t V, int32_t dtype,
+                        float* d_logp_k, float* d_entropy_k, void* d_ws, size_t ws_bytes, void* stream);
+
+/*
  * Workspace for nat_loss_fwd_bwd.  *_bytes is the recommended size (largest
  * token chunk the kernels use); *_min_bytes the smallest size accepted (one
  * token tile per chunk).  Both return 0 for unsupported arguments.

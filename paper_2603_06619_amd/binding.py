@@ -94,6 +94,11 @@ def load_library():
     lib.nat_loss_fwd_bwd_kl.restype = i32
     lib.nat_loss_fwd_bwd_kl.argtypes = [vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, f32, f32, f32,
                                         vp, f32, i32, vp, vp, vp, vp, vp, vp, i32, vp, sz, vp]
+    for name in ("nat_logp_workspace_bytes", "nat_logp_workspace_min_bytes"):
+        getattr(lib, name).restype = sz
+        getattr(lib, name).argtypes = [i32, i32, i32, i32]
+    lib.nat_logp_fwd.restype = i32
+    lib.nat_logp_fwd.argtypes = [vp, vp, vp, i32, i32, i32, i32, vp, vp, vp, sz, vp]
     lib.nat_profile_num_classes.restype = i32
     lib.nat_profile_class_name.restype = ctypes.c_char_p
     lib.nat_profile_class_name.argtypes = [i32]
@@ -245,6 +250,22 @@ def nat_loss_fwd_bwd_kl(hidden_k, W, ids_k, old_logp_k, adv, kept_seq, kept_w, N
         int(accumulate_dw), _ptr(workspace),
         workspace.numel() * workspace.element_size() if workspace is not None else 0, _stream()),
         "nat_loss_fwd_bwd_kl")
+
+
+def logp_workspace_bytes(N_k, H, V, dtype):
+    return int(load_library().nat_logp_workspace_bytes(int(N_k), int(H), int(V), int(dtype)))
+
+
+def logp_workspace_min_bytes(N_k, H, V, dtype):
+    return int(load_library().nat_logp_workspace_min_bytes(int(N_k), int(H), int(V), int(dtype)))
+
+
+def nat_logp_fwd(hidden_k, W, ids_k, N_k, logp_out, entropy_out, workspace):
+    V, H = W.shape
+    _raise(load_library().nat_logp_fwd(
+        _ptr(hidden_k), _ptr(W), _ptr(ids_k), N_k, H, V, _dtype_code(W), _ptr(logp_out), _ptr(entropy_out),
+        _ptr(workspace), workspace.numel() * workspace.element_size() if workspace is not None else 0, _stream()),
+        "nat_logp_fwd")
 
 
 def profile_enable(on):

@@ -121,6 +121,35 @@ extern "C" size_t nat_loss_workspace_min_bytes(int32_t N_k, int32_t H, int32_t V
   return 0;
 }
 
+extern "C" size_t nat_logp_workspace_bytes(int32_t N_k, int32_t H, int32_t V, int32_t dtype) {
+  if (N_k < 0 || H <= 0 || V <= 0) return 0;
+  if (dtype == NAT_DTYPE_BF16) return (H % 64) ? 0 : logp_bf16_workspace_bytes(N_k, H, V, false);
+  if (dtype == NAT_DTYPE_F32) return logp_f32_workspace_bytes(N_k, H, V, false);
+  return 0;
+}
+
+extern "C" size_t nat_logp_workspace_min_bytes(int32_t N_k, int32_t H, int32_t V, int32_t dtype) {
+  if (N_k < 0 || H <= 0 || V <= 0) return 0;
+  if (dtype == NAT_DTYPE_BF16) return (H % 64) ? 0 : logp_bf16_workspace_bytes(N_k, H, V, true);
+  if (dtype == NAT_DTYPE_F32) return logp_f32_workspace_bytes(N_k, H, V, true);
+  return 0;
+}
+
+extern "C" nat_status nat_logp_fwd(const void* d_hidden_k, const void* d_W, const int32_t* d_ids_k,
+                                   int32_t N_k, int32_t H, int32_t V, int32_t dtype,
+                                   float* d_logp_k, float* d_entropy_k, void* d_ws, size_t ws_bytes, void* stream) {
+  if (dtype != NAT_DTYPE_F32 && dtype != NAT_DTYPE_BF16) return NAT_UNSUPPORTED_DTYPE;
+  if (N_k < 0) return NAT_INVALID_ARG;
+  if (H <= 0 || V <= 0) return NAT_BAD_SHAPE;
+  if (dtype == NAT_DTYPE_BF16 && (H % 64) != 0) return NAT_BAD_SHAPE;
+  if (N_k == 0) return NAT_OK;
+  if (!d_hidden_k || !d_W || !d_ids_k || !d_logp_k) return NAT_INVALID_ARG;
+  if (!d_ws || ws_bytes < nat_logp_workspace_min_bytes(N_k, H, V, dtype)) return NAT_WORKSPACE_TOO_SMALL;
+  if (((uintptr_t)d_ws & 255) || ((uintptr_t)d_hidden_k & 15) || ((uintptr_t)d_W & 15)) return NAT_INVALID_ARG;
+  LogpArgs a{d_hidden_k, d_W, d_ids_k, N_k, H, V, d_logp_k, d_entropy_k, d_ws, ws_bytes, (hipStream_t)stream};
+  return dtype == NAT_DTYPE_BF16 ? logp_bf16_run(a) : logp_f32_run(a);
+}
+
 extern "C" nat_status nat_loss_fwd_bwd_kl(const void* d_hidden_k, const void* d_W, const int32_t* d_ids_k,
                                           const float* d_old_logp_k, const float* d_adv, const int32_t* d_kept_seq,
                                           const float* d_kept_w, int32_t N_k, int32_t H, int32_t V, int32_t dtype,

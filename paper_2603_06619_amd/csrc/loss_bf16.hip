@@ -311,7 +311,7 @@ gemm_nt_kernel(GemmArgs g, Epilogue epi) {
 // ------------------------------------------------------------- epilogues ----
 
 // Logits tile: rows = vocabulary (A = W), columns = tokens of the chunk (B = H_chunk).
-template <bool kEntropy>
+template <bool kEntropy, bool kStoreE = true>
 struct LogitsEpilogue {
   int V, n_valid;                  // vocabulary size, valid tokens in the chunk
   int64_t ld_part;                 // leading dimension (tokens) of the partial sums
@@ -398,6 +398,8 @@ struct LogitsEpilogue {
         if (lhi == 0) t_part[(int64_t)granule * ld_part + kk] = t;
       }
     }
+
+    if (!kStoreE) return;                                  // forward pass alone: the sums are all that is kept
 
     // Et (rows = vocabulary, k = token): neighbouring lanes hold neighbouring tokens; an exchange
     // with lane^1 lets even lanes store rows r (two tokens, 4 bytes) and odd lanes rows r+1.
@@ -574,6 +576,31 @@ token_stats_kernel(const float* __restrict__ s_part, const float* __restrict__ t
   term[k] = w * ts.L;
 }
 
+// Forward pass alone: log-prob of the target (and the entropy) from the per-granule sums.
+__global__ void __launch_bounds__(256)
+logp_stats_kernel(const float* __restrict__ s_part, const float* __restrict__ t_part, int n_granules, int64_t ld,
+                  const float* __restrict__ ref, const float* __restrict__ z_target, int n_valid, int chunk_start,
+                  float* __restrict__ logp_out, float* __restrict__ entropy_out) {
+  __shared__ float s_s[4][64];
+  __shared__ float t_s[4][64];
+  const int t = threadIdx.x & 63, part = threadIdx.x >> 6;
+  const int kk = blockIdx.x * 64 + t;
+  float s = 0.f, tz = 0.f;
+  if (kk < n_valid) {
+    for (int gi = part; gi < n_granules; gi += 4) s += s_part[(int64_t)gi * ld + kk];
+    if (t_part)
+      for (int gi = part; gi < n_granules; gi += 4) tz += t_part[(int64_t)gi * ld + kk];
+  }
+  s_s[part][t] = s;
+  t_s[part][t] = tz;
+  __syncthreads();
+  if (part != 0 || kk >= n_valid) return;
+  const float S = (s_s[0][t] + s_s[1][t]) + (s_s[2][t] + s_s[3][t]);
+  const int k = chunk_start + kk;
+  logp_out[k] = z_target[kk] - (ref[kk] + logf(S));
+  if (entropy_out) entropy_out[k] = logf(S) - ((t_s[0][t] + t_s[1][t]) + (t_s[2][t] + t_s[3][t])) / S;
+}
+
 // Overwrite the target entry of every valid token in both copies of E (see token_stats_kernel).
 __global__ void __launch_bounds__(256)
 patch_target_kernel(uint16_t* __restrict__ Et, int kb_e, uint16_t* __restrict__ Eb, int kb_z,
@@ -626,6 +653,30 @@ static int recommended_cap(int32_t N_k) {
 
 size_t loss_bf16_workspace_bytes(int32_t N_k, int32_t H, int32_t V, bool minimal) {
   return make_plan(N_k, H, V, minimal ? kBN : recommended_cap(N_k)).total;
+}
+
+// workspace of the forward pass alone: W and H_chunk blocked, the partial sums, two per-token vectors
+struct FwdPlan { int64_t Vp; int n_granules; int cap; size_t off_Wb, off_Hb, off_s, off_t, off_zt, off_ref, total; };
+
+static FwdPlan make_fwd_plan(int32_t H, int32_t V, int cap) {
+  FwdPlan p;
+  p.Vp = round_up(V, kBM);
+  p.n_granules = (int)(p.Vp / kGranule);
+  p.cap = cap;
+  size_t off = 0;
+  auto take = [&](size_t bytes) { size_t o = off; off += (bytes + 255) / 256 * 256; return o; };
+  p.off_Wb = take((size_t)p.Vp * H * 2);
+  p.off_Hb = take((size_t)cap * H * 2);
+  p.off_s = take((size_t)p.n_granules * cap * 4);
+  p.off_t = take((size_t)p.n_granules * cap * 4);
+  p.off_zt = take((size_t)cap * 4);
+  p.off_ref = take((size_t)cap * 4);
+  p.total = off;
+  return p;
+}
+
+size_t logp_bf16_workspace_bytes(int32_t N_k, int32_t H, int32_t V, bool minimal) {
+  return make_fwd_plan(H, V, minimal ? kBN : recommended_cap(N_k)).total;
 }
 
 template <int NW, class Epi>
@@ -721,6 +772,61 @@ nat_status loss_bf16_run(const LossArgs& a) {
   ProfScope prof(PC_LOSS_REDUCE, s);
   loss_reduce_kernel<<<1, 1024, 0, s>>>(term, a.N_k, a.loss);
   NAT_LAUNCH_CHECK();
+  return NAT_OK;
+}
+
+
+nat_status logp_bf16_run(const LogpArgs& a) {
+  int cap = recommended_cap(a.N_k);
+  while (cap > kBN && make_fwd_plan(a.H, a.V, cap).total > a.ws_bytes) cap -= kBN;
+  const FwdPlan p = make_fwd_plan(a.H, a.V, cap);
+  if (p.total > a.ws_bytes) return NAT_WORKSPACE_TOO_SMALL;
+  hipStream_t s = a.stream;
+  char* ws = (char*)a.ws;
+  uint16_t* Wb = (uint16_t*)(ws + p.off_Wb);
+  uint16_t* Hb = (uint16_t*)(ws + p.off_Hb);
+  float* s_part = (float*)(ws + p.off_s);
+  float* t_part = a.entropy ? (float*)(ws + p.off_t) : nullptr;
+  float* zt = (float*)(ws + p.off_zt);
+  float* ref = (float*)(ws + p.off_ref);
+  const uint16_t* W = (const uint16_t*)a.W;
+  const uint16_t* hidden = (const uint16_t*)a.hidden;
+  const int H = a.H, V = a.V, Vp = (int)p.Vp;
+  {
+    ProfScope prof(PC_TRANSPOSE, s);
+    pack_blocked_kernel<<<dim3(Vp / 64, H / 64), 256, 0, s>>>(W, H, V, H, Vp, H, Wb, nullptr, nullptr);
+    NAT_LAUNCH_CHECK();
+  }
+  for (int c0 = 0; c0 < a.N_k; c0 += cap) {
+    const int nv = a.N_k - c0 < cap ? a.N_k - c0 : cap;
+    const int np = (int)round_up(nv, kBN);
+    const uint16_t* hid_c = hidden + (int64_t)c0 * H;
+    {
+      ProfScope prof(PC_TRANSPOSE, s);
+      pack_blocked_kernel<<<dim3(np / 64, H / 64), 256, 0, s>>>(hid_c, H, nv, H, np, H, Hb, nullptr, nullptr);
+      NAT_LAUNCH_CHECK();
+      target_logit_kernel<<<(nv + 3) / 4, 256, 0, s>>>(hid_c, W, a.ids + c0, nv, H, ref);
+      NAT_LAUNCH_CHECK();
+    }
+    {
+      GemmArgs g{Wb, Hb, H, Vp / kBM, np / kBN, NAT_GROUP_LOGITS};
+      nat_status st;
+      if (t_part) {
+        LogitsEpilogue<true, false> e{V, nv, cap, 0, 0, nullptr, nullptr, s_part, t_part, zt, a.ids + c0, ref};
+        st = launch_gemm<NAT_WAVES_LOGITS>(g, e, PC_LOGITS, s);
+      } else {
+        LogitsEpilogue<false, false> e{V, nv, cap, 0, 0, nullptr, nullptr, s_part, nullptr, zt, a.ids + c0, ref};
+        st = launch_gemm<NAT_WAVES_LOGITS>(g, e, PC_LOGITS, s);
+      }
+      if (st != NAT_OK) return st;
+    }
+    {
+      ProfScope prof(PC_TOKEN_STATS, s);
+      logp_stats_kernel<<<(nv + 63) / 64, 256, 0, s>>>(s_part, t_part, p.n_granules, cap, ref, zt, nv, c0, a.logp,
+                                                      a.entropy);
+      NAT_LAUNCH_CHECK();
+    }
+  }
   return NAT_OK;
 }
 

@@ -157,4 +157,74 @@ nat_status loss_f32_run(const LossArgs& a) {
   return NAT_OK;
 }
 
+
+// Forward pass alone on the fp32 path: one block per token, logits kept in LDS-sized pieces of the
+// chunk scratch, log-sum-exp with the true row maximum, entropy from the same two sums.
+__global__ void __launch_bounds__(kF32Threads)
+f32_logp_kernel(const float* __restrict__ hidden, const float* __restrict__ W, const int32_t* __restrict__ ids,
+                int chunk_start, int H, int V, float* __restrict__ z_scratch /*[chunk, V]*/,
+                float* __restrict__ logp_out, float* __restrict__ entropy_out) {
+  extern __shared__ float h_s[];
+  __shared__ float red[4], red_t[4];
+  const int kc = blockIdx.x, k = chunk_start + kc;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  for (int h = threadIdx.x; h < H; h += kF32Threads) h_s[h] = hidden[(size_t)k * H + h];
+  __syncthreads();
+  float* z = z_scratch + (size_t)kc * V;
+  for (int v = wave; v < V; v += 4) {
+    const float* wr = W + (size_t)v * H;
+    float p = 0.f;
+    for (int h = lane; h < H; h += 64) p = fmaf(wr[h], h_s[h], p);
+    p = wave_sum_f(p);
+    if (lane == 0) z[v] = p;
+  }
+  __syncthreads();
+  float m = -INFINITY;
+  for (int v = threadIdx.x; v < V; v += kF32Threads) m = fmaxf(m, z[v]);
+  m = wave_max_f(m);
+  if (lane == 0) red[wave] = m;
+  __syncthreads();
+  m = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+  __syncthreads();
+  float s = 0.f, t = 0.f;
+  for (int v = threadIdx.x; v < V; v += kF32Threads) {
+    const float zc = z[v] - m, e = expf(zc);
+    s += e;
+    t = fmaf(e, zc, t);
+  }
+  s = wave_sum_f(s);
+  t = wave_sum_f(t);
+  if (lane == 0) { red[wave] = s; red_t[wave] = t; }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    const float sum = (red[0] + red[1]) + (red[2] + red[3]);
+    logp_out[k] = z[ids[k]] - (m + logf(sum));
+    if (entropy_out) entropy_out[k] = logf(sum) - ((red_t[0] + red_t[1]) + (red_t[2] + red_t[3])) / sum;
+  }
+}
+
+size_t logp_f32_workspace_bytes(int32_t N_k, int32_t H, int32_t V, bool minimal) {
+  (void)H;
+  int rows = N_k < 1 ? 1 : N_k;
+  const int cap = minimal ? 1 : 4096;
+  if (rows > cap) rows = cap;
+  return 256 + (size_t)rows * V * sizeof(float);
+}
+
+nat_status logp_f32_run(const LogpArgs& a) {
+  if ((size_t)a.H * sizeof(float) > 60 * 1024) return NAT_BAD_SHAPE;
+  if (a.ws_bytes < 256 + (size_t)a.V * sizeof(float)) return NAT_WORKSPACE_TOO_SMALL;
+  size_t rows = (a.ws_bytes - 256) / ((size_t)a.V * sizeof(float));
+  if (rows > (size_t)a.N_k) rows = a.N_k;
+  hipStream_t s = a.stream;
+  ProfScope prof(PC_F32_PATH, s);
+  for (int c0 = 0; c0 < a.N_k; c0 += (int)rows) {
+    const int n = a.N_k - c0 < (int)rows ? a.N_k - c0 : (int)rows;
+    f32_logp_kernel<<<n, kF32Threads, (size_t)a.H * sizeof(float), s>>>(
+        (const float*)a.hidden, (const float*)a.W, a.ids, c0, a.H, a.V, (float*)a.ws, a.logp, a.entropy);
+    NAT_LAUNCH_CHECK();
+  }
+  return NAT_OK;
+}
+
 }  // namespace nat

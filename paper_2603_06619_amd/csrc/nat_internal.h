@@ -75,6 +75,16 @@ nat_status loss_bf16_run(const LossArgs& a);
 size_t loss_f32_workspace_bytes(int32_t N_k, int32_t H, int32_t V, bool minimal);
 nat_status loss_f32_run(const LossArgs& a);
 
+// forward pass alone (log-prob of given tokens, optional entropy)
+struct LogpArgs {
+  const void* hidden; const void* W; const int32_t* ids; int32_t N_k, H, V;
+  float* logp; float* entropy; void* ws; size_t ws_bytes; hipStream_t stream;
+};
+size_t logp_bf16_workspace_bytes(int32_t N_k, int32_t H, int32_t V, bool minimal);
+nat_status logp_bf16_run(const LogpArgs& a);
+size_t logp_f32_workspace_bytes(int32_t N_k, int32_t H, int32_t V, bool minimal);
+nat_status logp_f32_run(const LogpArgs& a);
+
 // shared small kernels (api.hip)
 nat_status fill_zero_f32(float* p, size_t n, hipStream_t s);
 

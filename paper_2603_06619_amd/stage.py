@@ -85,6 +85,19 @@ class LossStage:
         out["total"], out["max_len"] = int(self.h_totals[0]), int(self.h_totals[1])
         return out
 
+    def logp(self, hidden_k, W, ids_k, N_k, want_entropy=False, ws_bytes=None):
+        """Forward pass alone: log-probs (and entropies) of the given tokens."""
+        dev = self.device
+        V, H = W.shape
+        dt = nb.DTYPE_BF16 if W.dtype == torch.bfloat16 else nb.DTYPE_F32
+        if ws_bytes is None:
+            ws_bytes = nb.logp_workspace_bytes(N_k, H, V, dt)
+        ws = self._buf("loss", max(ws_bytes, 256))[:max(ws_bytes, 256)]
+        out = dict(logp=torch.empty(max(N_k, 1), dtype=torch.float32, device=dev),
+                   entropy=torch.empty(max(N_k, 1), dtype=torch.float32, device=dev) if want_entropy else None)
+        nb.nat_logp_fwd(hidden_k, W, ids_k, N_k, out["logp"], out["entropy"], ws)
+        return out
+
     def loss(self, hidden_k, W, ids_k, old_logp_k, adv, kept_seq, kept_w, N_k, eps_lo=0.2, eps_hi=0.2,
              grad_scale=1.0, dW=None, accumulate_dw=False, ws_bytes=None, want_logp=True,
              ref_logp_k=None, beta_kl=0.0, kl_kind=nb.KL_LOG_RATIO, want_kl=False, want_entropy=False):

@@ -157,6 +157,21 @@ def test_loss_kl_argument_errors(lib):
     assert call(ws_bytes=64) == 3
 
 
+def test_logp_fwd_argument_errors(lib):
+    fake = ctypes.c_void_p(256)
+    def call(N_k=10, H=64, V=512, dtype=1, hidden=fake, W=fake, logp=fake, ws=fake, ws_bytes=1 << 34):
+        return lib.nat_logp_fwd(hidden, W, fake, N_k, H, V, dtype, logp, None, ws, ws_bytes, None)
+    assert call(dtype=3) == 4
+    assert call(N_k=-1) == 1
+    assert call(H=100) == 2 and call(V=0) == 2
+    assert call(hidden=None) == 1 and call(logp=None) == 1
+    assert call(ws_bytes=100) == 3 and call(ws=None) == 3
+    assert call(W=ctypes.c_void_p(264)) == 1
+    assert call(N_k=0, hidden=None, ws=None) == 0            # nothing to do
+    assert lib.nat_logp_workspace_bytes(1000, 4096, 151936, 1) < lib.nat_loss_workspace_bytes(1000, 4096, 151936, 1)
+    assert lib.nat_logp_workspace_bytes(10, 100, 512, 1) == 0
+
+
 def test_profile_interface(lib):
     n = lib.nat_profile_num_classes()
     names = [lib.nat_profile_class_name(i) for i in range(n)]

@@ -63,6 +63,14 @@ constexpr int kTileBytes = kBM * kBK * 2;         // 16 KiB per operand per stag
 #endif
 constexpr int kMaxChunk = 32768;                  // token rows per chunk (recommended workspace)
 
+// two floats -> two bf16 in one 32-bit word (lo in bits 0..15): one packed conversion instruction
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+  typedef float f32x2 __attribute__((ext_vector_type(2)));
+  typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+  const f32x2 v = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
+}
+
 __device__ __forceinline__ uint16_t f32_to_bf16_bits(float x) {
   const __bf16 b = (__bf16)x;
   return __builtin_bit_cast(uint16_t, b);
@@ -415,7 +423,7 @@ struct LogitsEpilogue {
           const float give = odd ? x : yv;
           const float got = __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, give), 0xB1, 0xF, 0xF, true));
           const float lo = odd ? got : x, hi = odd ? yv : got;
-          const uint32_t packed = (uint32_t)f32_to_bf16_bits(lo) | ((uint32_t)f32_to_bf16_bits(hi) << 16);
+          const uint32_t packed = pack_bf16x2(lo, hi);
           const int v = v0 + mb * 32 + 8 * (r >> 2) + 4 * lhi + (r & 3) + (odd ? 1 : 0);
           *(uint32_t*)(Et + blk_off(v, kk_pair, kb_e)) = packed;
         }
@@ -436,8 +444,8 @@ struct LogitsEpilogue {
           for (int r4 = 0; r4 < 4; ++r4) {
             const f32x16& a = acc[half * 2 + mbh][nb];
             uint2 w;
-            w.x = (uint32_t)f32_to_bf16_bits(a[4 * r4]) | ((uint32_t)f32_to_bf16_bits(a[4 * r4 + 1]) << 16);
-            w.y = (uint32_t)f32_to_bf16_bits(a[4 * r4 + 2]) | ((uint32_t)f32_to_bf16_bits(a[4 * r4 + 3]) << 16);
+            w.x = pack_bf16x2(a[4 * r4], a[4 * r4 + 1]);
+            w.y = pack_bf16x2(a[4 * r4 + 2], a[4 * r4 + 3]);
             *(uint2*)(stage + (nb * 32 + l32) * kStageRow + (mbh * 32 + 8 * r4 + 4 * lhi) * 2) = w;
           }
       __syncthreads();

@@ -3,6 +3,10 @@
  * are Needed") for AMD MI355X (gfx950).
  *
  * Path:  rewards -> nat_advantage -> nat_select -> nat_compact -> nat_loss_fwd_bwd
+ * Around it: nat_select_schedule / nat_select_poisson + nat_compact_pi (other selection
+ * laws inside the same estimator), nat_prefix_pack (the truncated batch for the model
+ * body), nat_loss_fwd_bwd_kl (token loss with the KL term, entropy), nat_logp_fwd (the
+ * forward pass alone).
  *
  * Notation follows the paper: P prompts, G rollouts per prompt, B = P*G
  * rollouts, T_i response length of rollout i, t = 1..T_i token position,

@@ -32,6 +32,10 @@ namespace nat {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x4v __attribute__((ext_vector_type(4)));
+// The soft-max numerators are written once and read back only by the two backward contractions,
+// long after they have left the L2: non-temporal stores (1 % on the logits kernel).
+#define NAT_E_STORE(ptr, val) __builtin_nontemporal_store((val), (ptr))
 
 constexpr int kBM = 256, kBN = 256, kBK = 32;     // block tile: 4 wavefronts of 128 x 128 or 8 of 128 x 64
 constexpr int kStages = 4;                        // LDS ring of k-slices (4 x 32 KiB)
@@ -425,7 +429,7 @@ struct LogitsEpilogue {
           const float lo = odd ? got : x, hi = odd ? yv : got;
           const uint32_t packed = pack_bf16x2(lo, hi);
           const int v = v0 + mb * 32 + 8 * (r >> 2) + 4 * lhi + (r & 3) + (odd ? 1 : 0);
-          *(uint32_t*)(Et + blk_off(v, kk_pair, kb_e)) = packed;
+          NAT_E_STORE((uint32_t*)(Et + blk_off(v, kk_pair, kb_e)), packed);
         }
     }
 
@@ -454,7 +458,7 @@ struct LogitsEpilogue {
         const int q = i * 64 + lane;                    // slice q/(4 kTok), token (q%(4 kTok))/4, 16-byte chunk q%4
         const int sl = q / (4 * kTok), tok = (q % (4 * kTok)) >> 2, ch = q & 3;
         const uint4 val = *(const uint4*)(stage + tok * kStageRow + sl * 64 + ch * 16);
-        *(uint4*)(Eb + blk_off(k0 + tok, v0 + half * 64 + sl * 32 + ch * 8, kb_z)) = val;
+        NAT_E_STORE((u32x4v*)(Eb + blk_off(k0 + tok, v0 + half * 64 + sl * 32 + ch * 8, kb_z)), __builtin_bit_cast(u32x4v, val));
       }
     }
   }

@@ -1,6 +1,8 @@
-// bf16 path of nat_loss_fwd_bwd for gfx950: LM-head projection, full-vocabulary
-// log-softmax, clipped GRPO surrogate with Horvitz-Thompson weights (Eq. 1, 3, 5,
-// 6/9) and the gradients dH, dW (App. A) on the kept tokens.
+// bf16 path of nat_loss_fwd_bwd / nat_loss_fwd_bwd_kl / nat_logp_fwd for gfx950: LM-head
+// projection, full-vocabulary log-softmax, clipped GRPO surrogate with Horvitz-Thompson
+// weights (Eq. 1, 3, 5, 6/9), optional KL term (Eq. 4) and entropy, and the gradients dH, dW
+// (App. A) on the kept tokens.  The forward pass alone runs the first two steps below and
+// keeps only the sums.
 //
 // Tokens are processed in chunks of at most `cap` rows.  Per chunk:
 //   reference     ref_k = h_k . W[ids_k]: the target logit, used only as the exponent shift;

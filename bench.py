@@ -64,6 +64,9 @@ def parse_args():
     ap.add_argument("--kl-beta", type=float, default=0.0,
                     help="weight of the KL term of the token loss (reference log-probs are synthetic); 0 = off")
     ap.add_argument("--entropy", action="store_true", help="also accumulate the per-token entropy in the sweep")
+    ap.add_argument("--logp-noise-scale", type=float, default=1.0,
+                    help="multiplies the N(0, 0.05) noise of the behaviour log-probs (4 puts ~1/3 of the tokens on the "
+                         "clipped branch at eps = 0.2)")
     ap.add_argument("--forward-only", action="store_true",
                     help="time nat_logp_fwd (log-probs of the kept tokens, 2VH flops per token) instead of the loss")
     ap.add_argument("--prefix-pack", action="store_true",
@@ -224,7 +227,8 @@ def main():
     args.scheme_name = scheme_name
     batch = si.make_batch_torch(args.workload, args.seed, dev, P=args.prompts)
     P, G, B, N, H, V = batch["P"], batch["G"], batch["B"], batch["N"], batch["H"], batch["V"]
-    old_logp = si.behaviour_logp_stand_in(batch["hidden"], batch["W"], batch["ids"], batch["logp_noise"])
+    old_logp = si.behaviour_logp_stand_in(batch["hidden"], batch["W"], batch["ids"],
+                                          batch["logp_noise"] * args.logp_noise_scale)
     rewards = torch.from_numpy(batch["rewards"].reshape(-1)).to(dev)
     cu = torch.from_numpy(batch["cu_seqlens"]).to(dev)
     spr = None
@@ -318,7 +322,7 @@ def main():
                    "p": args.p if scheme_name == "urs" else None, "min_cut": args.min_cut if scheme_name == "rpc" else None,
                    "kl_beta": args.kl_beta, "entropy": bool(args.entropy),
                    "drop_zero_adv": bool(args.drop_zero_adv),
-                   "forward_only": bool(args.forward_only)},
+                   "forward_only": bool(args.forward_only), "logp_noise_scale": args.logp_noise_scale},
         "mfma_util_pct_useful_6VH": 100.0 * useful_tflops / PEAK_BF16_TFLOPS,
         "mfma_util_pct_gemm_kernels_only": (100.0 * 2.0 * n_gemms * V * H * kept_total / (gemm_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS
                                             if gemm_ms > 0 else None),

@@ -135,7 +135,9 @@ def test_sampled_tokens_with_kl_term_and_entropy_at_full_size(full_run):
     gen = torch.Generator(device=DEV)
     gen.manual_seed(5)
     ref_lp = sc["old_logp_k"] + 0.1 * torch.randn(sc["old_logp_k"].shape, generator=gen, device=DEV)
-    out = LossStage(DEV).loss(sc["hidden_k"], b["W"], sc["ids_k"], sc["old_logp_k"], full_run["adv"], sc["kept_seq"],
+    # behaviour log-probs off by N(0, 0.2): about a third of the tokens sit on the clipped branch
+    old_noisy = sc["old_logp_k"] + 0.2 * torch.randn(sc["old_logp_k"].shape, generator=gen, device=DEV)
+    out = LossStage(DEV).loss(sc["hidden_k"], b["W"], sc["ids_k"], old_noisy, full_run["adv"], sc["kept_seq"],
                               sc["kept_w"], nk, ref_logp_k=ref_lp, beta_kl=0.04, kl_kind=ogrpo.KL_NONNEG,
                               want_kl=True, want_entropy=True)
     torch.cuda.synchronize()
@@ -144,10 +146,12 @@ def test_sampled_tokens_with_kl_term_and_entropy_at_full_size(full_run):
     sidx = torch.from_numpy(sample).to(DEV)
     adv = full_run["adv"].cpu().numpy().astype(np.float64)
     ref = ogrpo.loss_and_grads(sc["hidden_k"][sidx].float().cpu().numpy(), b["W"].float().cpu().numpy(),
-                               sc["ids_k"][sidx].cpu().numpy(), sc["old_logp_k"][sidx].cpu().numpy(),
+                               sc["ids_k"][sidx].cpu().numpy(), old_noisy[sidx].cpu().numpy(),
                                adv[sc["kept_seq"][sidx].cpu().numpy()], sc["kept_w"][sidx].cpu().numpy().astype(np.float64),
                                ref_logp=ref_lp[sidx].cpu().numpy(), beta_kl=0.04, kl_kind=ogrpo.KL_NONNEG)
     assert np.abs(out["logp"][sidx].cpu().numpy() - ref["logp"]).max() < 5e-3
+    clipped = (ref["r"] > 1.2) | (ref["r"] < 0.8)
+    assert clipped.sum() >= 2 and (~clipped).sum() >= 2          # both branches of Eq. 3 among the samples
     ent = out["entropy"][sidx].cpu().numpy()
     assert np.abs(ent - ref["entropy"]).max() <= 1e-4 * np.abs(ref["entropy"]).max()
     assert np.abs(out["kl"][sidx].cpu().numpy() - ref["kl"]).max() <= 1e-4 * np.abs(ref["kl"]).max() + 2e-6

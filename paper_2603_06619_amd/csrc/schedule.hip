@@ -96,28 +96,56 @@ schedule_cut_kernel(uint32_t key0, uint32_t key1, uint32_t step, int32_t rollout
   }
 }
 
+// Four consecutive packed positions per lane (one Philox block serves four consecutive tokens of a
+// rollout); the 16 lanes of a 64-token group OR their nibbles into the two mask words.
 __global__ void __launch_bounds__(256)
 poisson_mask_kernel(uint32_t key0, uint32_t key1, uint32_t step, int32_t rollout_id_base,
-                    const float* __restrict__ drop_zero_adv, const double* __restrict__ pi, const int64_t* __restrict__ cu, int B, int64_t N,
-                    uint32_t* __restrict__ mask_bits) {
-  const int64_t n = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  bool keep = false;
-  if (n < N) {
-    const int i = rollout_of_pos(cu, 0, B, n);
-    const int64_t t0 = n - cu[i];
-    const double p = pi[n];
-    uint64_t thr = 0;                                           // p <= 0 or NaN: never keep
-    if (p >= 1.0) thr = 1ull << 32;
-    else if (p > 0.0) thr = (uint64_t)floor(p * 4294967296.0);
-    const u32x4 r = philox4x32_10(u32x4{(uint32_t)(t0 >> 2), (uint32_t)(rollout_id_base + i), 0u, step}, key0, key1);
-    const uint32_t word = (t0 & 3) == 0 ? r.x : (t0 & 3) == 1 ? r.y : (t0 & 3) == 2 ? r.z : r.w;
-    keep = (uint64_t)word < thr && !(drop_zero_adv && drop_zero_adv[i] == 0.f);
+                    const float* __restrict__ drop_zero_adv, const double* __restrict__ pi,
+                    const int64_t* __restrict__ cu, int B, int64_t N, uint32_t* __restrict__ mask_bits) {
+  const int64_t n0 = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4;
+  uint32_t nibble = 0;
+  if (n0 < N) {
+    int i = rollout_of_pos(cu, 0, B, n0);
+    int64_t start = cu[i], end = cu[i + 1];
+    bool dropped = drop_zero_adv && drop_zero_adv[i] == 0.f;
+    u32x4 r{0u, 0u, 0u, 0u};
+    int64_t have_block = -1;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int64_t n = n0 + j;
+      if (n >= N) break;
+      if (n >= end) {
+        do { ++i; } while (cu[i + 1] <= n);
+        start = cu[i];
+        end = cu[i + 1];
+        dropped = drop_zero_adv && drop_zero_adv[i] == 0.f;
+        have_block = -1;
+      }
+      const int64_t t0 = n - start;
+      if ((t0 >> 2) != have_block) {
+        have_block = t0 >> 2;
+        r = philox4x32_10(u32x4{(uint32_t)have_block, (uint32_t)(rollout_id_base + i), 0u, step}, key0, key1);
+      }
+      const double p = pi[n];
+      uint64_t thr = 0;                                           // p <= 0 or NaN: never keep
+      if (p >= 1.0) thr = 1ull << 32;
+      else if (p > 0.0) thr = (uint64_t)floor(p * 4294967296.0);
+      const uint32_t word = (t0 & 3) == 0 ? r.x : (t0 & 3) == 1 ? r.y : (t0 & 3) == 2 ? r.z : r.w;
+      if ((uint64_t)word < thr && !dropped) nibble |= 1u << j;
+    }
   }
-  const uint64_t ballot = __ballot(keep);
-  if ((threadIdx.x & 63) == 0 && n < N) {
-    const int64_t group = n >> 6;
-    mask_bits[2 * group] = (uint32_t)ballot;
-    mask_bits[2 * group + 1] = (uint32_t)(ballot >> 32);
+  const int sub = threadIdx.x & 15;
+  uint32_t lo = sub < 8 ? nibble << (4 * sub) : 0u;
+  uint32_t hi = sub >= 8 ? nibble << (4 * (sub - 8)) : 0u;
+#pragma unroll
+  for (int off = 1; off < 16; off <<= 1) {
+    lo |= __shfl_xor(lo, off);
+    hi |= __shfl_xor(hi, off);
+  }
+  if (sub == 0 && n0 < N) {
+    const int64_t group = n0 >> 6;
+    mask_bits[2 * group] = lo;
+    mask_bits[2 * group + 1] = hi;
   }
 }
 
@@ -228,7 +256,7 @@ extern "C" nat_status nat_select_poisson(const nat_select_params* params, const 
   if (N == 0) return NAT_OK;
   hipStream_t s = (hipStream_t)stream;
   ProfScope prof(PC_SCHEDULE, s);
-  poisson_mask_kernel<<<(unsigned)((N + 255) / 256), 256, 0, s>>>(
+  poisson_mask_kernel<<<(unsigned)((N + 1023) / 1024), 256, 0, s>>>(
       (uint32_t)(params->seed & 0xFFFFFFFFull), (uint32_t)(params->seed >> 32), params->step,
       params->rollout_id_base, params->d_drop_zero_adv, d_pi, d_cu_seqlens, B, N, d_mask_bits);
   NAT_LAUNCH_CHECK();

@@ -1,7 +1,7 @@
 // nat_advantage and nat_select: group-relative advantage (Eq. 2) and the token
 // selection mask of Sec. 3.1 (URS) and Sec. 4 (RPC, Eq. 7; deterministic
-// truncation).  One lane per packed token position; a wavefront ballot packs
-// 64 mask bits into two 32-bit words.
+// truncation).  Four packed token positions per lane; the 16 lanes of a 64-token
+// group combine their bits into two 32-bit mask words.
 #include "nat_internal.h"
 #include "philox.hip.h"
 
@@ -46,33 +46,71 @@ __global__ void select_cut_kernel(SelectArgs a, const int64_t* __restrict__ cu, 
   cut_len[i] = (int32_t)cut;
 }
 
+// Four consecutive packed positions per lane: the four words of one Philox block serve four
+// consecutive tokens of a rollout, so a lane evaluates one block (a second one where its
+// positions straddle a block or rollout boundary) and one rollout search instead of four.
+// A wavefront covers 256 positions = four 64-bit mask groups; the 16 lanes of a group OR
+// their nibbles together and the group's first lane writes the two words.
+constexpr int kSelPerLane = 4;
+constexpr int kSelPerBlock = 256 * kSelPerLane;
+
 __global__ void __launch_bounds__(256)
 select_mask_kernel(SelectArgs a, const int64_t* __restrict__ cu, int B, int64_t N,
                    const int32_t* __restrict__ cut_len, uint32_t* __restrict__ mask_bits) {
-  const int64_t n = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  bool keep = false;
-  if (n < N) {
-    const int i = rollout_of_pos(cu, 0, B, n);
-    const int64_t t0 = n - cu[i];
-    const int scheme = a.scheme_per_rollout ? a.scheme_per_rollout[i] : a.scheme;
-    if (scheme == NAT_SCHEME_URS) {
-      const u32x4 r = philox4x32_10(u32x4{(uint32_t)(t0 >> 2), (uint32_t)(a.rollout_id_base + i), 0u, a.step},
-                                    a.key0, a.key1);
-      const uint32_t lane_word = (t0 & 3) == 0 ? r.x : (t0 & 3) == 1 ? r.y : (t0 & 3) == 2 ? r.z : r.w;
-      keep = (uint64_t)lane_word < a.urs_threshold;
-    } else if (scheme == NAT_SCHEME_FULL) {
-      keep = true;
-    } else {
-      keep = t0 < (int64_t)cut_len[i];
+  const int64_t n0 = ((int64_t)blockIdx.x * 256 + threadIdx.x) * kSelPerLane;
+  uint32_t nibble = 0;
+  if (n0 < N) {
+    int i = rollout_of_pos(cu, 0, B, n0);
+    int64_t start = cu[i], end = cu[i + 1];
+    int scheme = a.scheme_per_rollout ? a.scheme_per_rollout[i] : a.scheme;
+    bool dropped = a.drop_zero_adv && a.drop_zero_adv[i] == 0.f;
+    int64_t cut = cut_len[i];
+    u32x4 r{0u, 0u, 0u, 0u};
+    int64_t have_block = -1;                       // index (t0 >> 2) of the block held in r, for rollout i
+#pragma unroll
+    for (int j = 0; j < kSelPerLane; ++j) {
+      const int64_t n = n0 + j;
+      if (n >= N) break;
+      if (n >= end) {                              // next non-empty rollout
+        do { ++i; } while (cu[i + 1] <= n);
+        start = cu[i];
+        end = cu[i + 1];
+        scheme = a.scheme_per_rollout ? a.scheme_per_rollout[i] : a.scheme;
+        dropped = a.drop_zero_adv && a.drop_zero_adv[i] == 0.f;
+        cut = cut_len[i];
+        have_block = -1;
+      }
+      const int64_t t0 = n - start;
+      bool keep;
+      if (scheme == NAT_SCHEME_URS) {
+        if ((t0 >> 2) != have_block) {
+          have_block = t0 >> 2;
+          r = philox4x32_10(u32x4{(uint32_t)have_block, (uint32_t)(a.rollout_id_base + i), 0u, a.step}, a.key0, a.key1);
+        }
+        const uint32_t word = (t0 & 3) == 0 ? r.x : (t0 & 3) == 1 ? r.y : (t0 & 3) == 2 ? r.z : r.w;
+        keep = (uint64_t)word < a.urs_threshold;
+      } else if (scheme == NAT_SCHEME_FULL) {
+        keep = true;
+      } else {
+        keep = t0 < cut;
+      }
+      if (keep && !dropped) nibble |= 1u << j;
     }
-    if (a.drop_zero_adv && a.drop_zero_adv[i] == 0.f) keep = false;
   }
-  const uint64_t ballot = __ballot(keep);
-  // groups past ceil(N/64) have no words in the mask (the last block may hold some)
-  if ((threadIdx.x & 63) == 0 && n < N) {
-    const int64_t group = n >> 6;
-    mask_bits[2 * group] = (uint32_t)ballot;
-    mask_bits[2 * group + 1] = (uint32_t)(ballot >> 32);
+  // lane l of a 16-lane group holds bits 4*(l%16) .. +3 of the group's 64-bit mask
+  const int sub = threadIdx.x & 15;
+  uint32_t lo = sub < 8 ? nibble << (4 * sub) : 0u;
+  uint32_t hi = sub >= 8 ? nibble << (4 * (sub - 8)) : 0u;
+#pragma unroll
+  for (int off = 1; off < 16; off <<= 1) {
+    lo |= __shfl_xor(lo, off);
+    hi |= __shfl_xor(hi, off);
+  }
+  // groups past ceil(N/64) have no words in the mask
+  if (sub == 0 && n0 < N) {
+    const int64_t group = n0 >> 6;
+    mask_bits[2 * group] = lo;
+    mask_bits[2 * group + 1] = hi;
   }
 }
 
@@ -101,7 +139,7 @@ nat_status launch_prefix_mask(const int64_t* d_cu, int32_t B, int64_t N, const i
   if (N <= 0) return NAT_OK;
   SelectArgs a{};
   a.scheme = NAT_SCHEME_DET;        // any prefix scheme: keep t0 < cut_len[i]
-  select_mask_kernel<<<(unsigned)((N + 255) / 256), 256, 0, s>>>(a, d_cu, B, N, d_cut_len, d_mask_bits);
+  select_mask_kernel<<<(unsigned)((N + kSelPerBlock - 1) / kSelPerBlock), 256, 0, s>>>(a, d_cu, B, N, d_cut_len, d_mask_bits);
   NAT_LAUNCH_CHECK();
   return NAT_OK;
 }
@@ -136,7 +174,7 @@ extern "C" nat_status nat_select(const nat_select_params* params, const int64_t*
   select_cut_kernel<<<(B + 255) / 256, 256, 0, s>>>(a, d_cu_seqlens, B, d_cut_len);
   NAT_LAUNCH_CHECK();
   if (N > 0) {
-    const int64_t blocks = (N + 255) / 256;
+    const int64_t blocks = (N + kSelPerBlock - 1) / kSelPerBlock;
     select_mask_kernel<<<(unsigned)blocks, 256, 0, s>>>(a, d_cu_seqlens, B, N, d_cut_len, d_mask_bits);
     NAT_LAUNCH_CHECK();
   }

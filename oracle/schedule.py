@@ -100,10 +100,14 @@ def schedule_q(a):
     return np.array([float(int(x)) / float(A) for x in a], dtype=np.float64)
 
 
-def select_schedule(cu_seqlens, weights, seed=0, step=0, rollout_id_base=0):
+def select_schedule(cu_seqlens, weights, seed=0, step=0, rollout_id_base=0, drop_zero_adv=None):
     """Cut every rollout of a packed batch by its own schedule.
 
     weights: [N] non-negative integers < 2**32 packed like the tokens.
+    drop_zero_adv: optional [B] advantages (Eq. 2); a rollout whose advantage is
+    exactly 0 keeps nothing (Eq. 3 with A = 0 gives S = 0 and a zero gradient at
+    each of its tokens): its mask is cleared and its cut set to 0, while the
+    survival function of every rollout, and so every weight, stays as it is.
     Returns dict(mask [N] bool, pi [N] fp64, cut_len [B] int32).
     """
     cu = np.asarray(cu_seqlens, dtype=np.int64)
@@ -115,6 +119,8 @@ def select_schedule(cu_seqlens, weights, seed=0, step=0, rollout_id_base=0):
         lo, hi = int(cu[i]), int(cu[i + 1])
         a = [int(x) for x in weights[lo:hi]]
         L = schedule_cut(a, seed, step, rollout_id_base + i)
+        if drop_zero_adv is not None and float(drop_zero_adv[i]) == 0.0:
+            L = 0
         cut[i] = L
         mask[lo:lo + L] = True
         pi[lo:hi] = schedule_pi(a)
@@ -145,12 +151,15 @@ def poisson_mask(pi, seed, step, rollout_id):
     return u < thr
 
 
-def select_poisson(cu_seqlens, pi, seed=0, step=0, rollout_id_base=0):
-    """Independent Bernoulli(pi_n) mask for a packed batch; returns mask [N] bool."""
+def select_poisson(cu_seqlens, pi, seed=0, step=0, rollout_id_base=0, drop_zero_adv=None):
+    """Independent Bernoulli(pi_n) mask for a packed batch; returns mask [N] bool.
+    drop_zero_adv: as in select_schedule (zero-advantage rollouts keep nothing)."""
     cu = np.asarray(cu_seqlens, dtype=np.int64)
     mask = np.zeros(int(cu[-1]), dtype=bool)
     for i in range(len(cu) - 1):
         lo, hi = int(cu[i]), int(cu[i + 1])
+        if drop_zero_adv is not None and float(drop_zero_adv[i]) == 0.0:
+            continue
         mask[lo:hi] = poisson_mask(np.asarray(pi[lo:hi], dtype=np.float64), seed, step, rollout_id_base + i)
     return mask
 

@@ -151,19 +151,14 @@ def test_schedule_and_poisson_drop_zero_advantage_rollouts(stage):
     adv = np.array([0.5, 0.0, -1.0, 0.0, 0.0, 2.0], dtype=np.float32)
     params = nat.SelectParams(nat.FULL, seed=8, step=1, drop_zero_adv=to_dev(adv))
     w = si.draw_schedule_weights(lengths, "random", seed=2)
-    o = osch.select_schedule(cu, w, seed=8, step=1)
-    for i in np.nonzero(adv == 0)[0]:                      # what the oracle's select does for such rollouts
-        o["mask"][cu[i]:cu[i + 1]] = False
-        o["cut_len"][i] = 0
+    o = osch.select_schedule(cu, w, seed=8, step=1, drop_zero_adv=adv)
     h = stage.select_compact(params, to_dev(cu), B, N, B, schedule_weights=to_dev(w.view(np.int32)))
     assert np.array_equal(h["cut_len"].cpu().numpy(), o["cut_len"])
     assert _mask_words(h, o["mask"])
     assert np.array_equal(h["pi"].cpu().numpy()[:N].view(np.uint64), o["pi"].view(np.uint64))
     _check_compact(h, osch.compact_pi(o["mask"], o["pi"], cu, B))
     pi = si.draw_inclusion_probs(N, seed=3)
-    m = osch.select_poisson(cu, pi, seed=8, step=1)
-    for i in np.nonzero(adv == 0)[0]:
-        m[cu[i]:cu[i + 1]] = False
+    m = osch.select_poisson(cu, pi, seed=8, step=1, drop_zero_adv=adv)
     h = stage.select_compact(params, to_dev(cu), B, N, B, poisson_pi=to_dev(pi))
     assert _mask_words(h, m)
     _check_compact(h, osch.compact_pi(m, pi, cu, B))

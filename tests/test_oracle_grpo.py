@@ -294,6 +294,35 @@ def test_monte_carlo_mean_converges_to_full_token(scheme, kw):
     std = np.sqrt(np.maximum(sq / K - mean ** 2, 0))
     ref = np.concatenate([[ft["loss"]], ft["dW"].ravel()])
     assert (np.abs(mean - ref) <= 5 * std / math.sqrt(K) + 1e-12).all()
-    # the driver form gives the same mean
-    mc = drivers.monte_carlo(b, scheme, list(seeds)[:50], **kw)
-    assert np.isfinite(mc["loss"])
+    # the driver form over the same seeds reproduces the running sums kept above
+    mc = drivers.monte_carlo(b, scheme, list(seeds), **kw)
+    assert np.isclose(mc["prob"], 1.0, rtol=0, atol=1e-12)
+    assert np.allclose(np.concatenate([[mc["loss"]], mc["dW"].ravel()]), mean, rtol=1e-11, atol=1e-15)
+    assert np.isclose(mc["loss_sq"], sq[0] / K, rtol=1e-11)
+    assert (np.abs(np.concatenate([[mc["loss"]], mc["dW"].ravel()]) - ref) <= 5 * std / math.sqrt(K) + 1e-12).all()
+
+
+def test_monte_carlo_driver_on_a_hand_enumerable_case():
+    # one rollout of two tokens under URS p = 1/2: the driver's mean over seeds is the average of the
+    # per-seed estimates, each of which is one of the four masks' estimates; and with p = 1 every
+    # draw is the full-token value
+    b = tiny_batch(43, [2], H=4, V=8)
+    pi = np.full(2, 0.5)
+    by_mask = {bits: drivers.estimate(b, np.array(bits), pi) for bits in
+               [(False, False), (False, True), (True, False), (True, True)]}
+    seeds = list(range(40))
+    want_loss, want_dW, want_sq = 0.0, 0.0, 0.0
+    seen = set()
+    for s in seeds:
+        m = tuple(bool(x) for x in sel.select(b["cu_seqlens"], sel.URS, p=0.5, seed=s)["mask"])
+        seen.add(m)
+        want_loss += by_mask[m]["loss"] / len(seeds)
+        want_dW = want_dW + by_mask[m]["dW"] / len(seeds)
+        want_sq += by_mask[m]["loss"] ** 2 / len(seeds)
+    assert len(seen) == 4                                   # every mask occurs among the draws
+    mc = drivers.monte_carlo(b, sel.URS, seeds, p=0.5)
+    assert np.isclose(mc["loss"], want_loss, rtol=1e-12) and np.isclose(mc["loss_sq"], want_sq, rtol=1e-12)
+    assert np.allclose(mc["dW"], want_dW, rtol=1e-12, atol=1e-18)
+    ft = drivers.full_token(b)
+    one = drivers.monte_carlo(b, sel.URS, [1, 2, 3], p=1.0)
+    assert np.isclose(one["loss"], ft["loss"], rtol=1e-13) and np.allclose(one["dW"], ft["dW"], rtol=1e-12, atol=1e-18)

@@ -279,3 +279,42 @@ def test_prefix_pack_rows_scale_with_the_cut_as_the_paper_states():
     resp_rows = out["total"] - 400 * 10
     assert abs(resp_rows / T.sum() - 0.5) < 0.05
     assert len(out["loss_row"]) == int(d["mask"].sum())
+
+
+# ------------------------------------------------- zero-advantage rollouts ----
+
+def test_schedule_and_poisson_dropping_zero_advantage_rollouts_leaves_the_estimate_unchanged():
+    # Eq. 3 with A = 0: S = 0 and dS/dlogp = 0 at every token of the rollout, whatever the ratio
+    b = tiny_batch(61, [5, 4, 6, 3])
+    b["adv"] = np.array([0.7, 0.0, -1.2, 0.0])
+    cu = b["cu_seqlens"]
+    N = int(cu[-1])
+    rng = np.random.default_rng(3)
+    w = rng.integers(1, 50, N).astype(np.uint32)
+    keep_all = sch.select_schedule(cu, w, seed=4, step=2)
+    dropped = sch.select_schedule(cu, w, seed=4, step=2, drop_zero_adv=b["adv"])
+    assert dropped["cut_len"].tolist() == [keep_all["cut_len"][0], 0, keep_all["cut_len"][2], 0]
+    assert not dropped["mask"][cu[1]:cu[2]].any() and not dropped["mask"][cu[3]:cu[4]].any()
+    for i in (0, 2):                                           # the other rollouts draw exactly as before
+        assert np.array_equal(dropped["mask"][cu[i]:cu[i + 1]], keep_all["mask"][cu[i]:cu[i + 1]])
+    assert np.array_equal(dropped["pi"], keep_all["pi"])       # survival functions (and weights) unchanged
+    e1 = drivers.estimate(b, keep_all["mask"], keep_all["pi"])
+    e2 = drivers.estimate(b, dropped["mask"], dropped["pi"])
+    assert abs(e1["loss"] - e2["loss"]) < 1e-15
+    assert np.abs(e1["dW"] - e2["dW"]).max() < 1e-15 and np.abs(e1["dH"] - e2["dH"]).max() < 1e-15
+
+    pi = 0.2 + 0.8 * rng.random(N)
+    m_all = sch.select_poisson(cu, pi, seed=9, step=1)
+    m_drop = sch.select_poisson(cu, pi, seed=9, step=1, drop_zero_adv=b["adv"])
+    assert m_all[cu[1]:cu[2]].any() and not m_drop[cu[1]:cu[2]].any() and not m_drop[cu[3]:cu[4]].any()
+    for i in (0, 2):
+        assert np.array_equal(m_drop[cu[i]:cu[i + 1]], m_all[cu[i]:cu[i + 1]])
+    e1 = drivers.estimate(b, m_all, pi)
+    e2 = drivers.estimate(b, m_drop, pi)
+    assert abs(e1["loss"] - e2["loss"]) < 1e-15 and np.abs(e1["dW"] - e2["dW"]).max() < 1e-15
+    # negative control: with a KL term the dropped tokens would have contributed
+    bk = dict(b, ref_logp=b["old_logp"] + 0.3, beta_kl=0.5, kl_kind=grpo.KL_NONNEG)
+    assert abs(drivers.estimate(bk, m_all, pi)["loss"] - drivers.estimate(bk, m_drop, pi)["loss"]) > 1e-4
+    # no advantages given, or none of them zero: nothing changes
+    same = sch.select_schedule(cu, w, seed=4, step=2, drop_zero_adv=np.array([0.7, 0.1, -1.2, 3.0]))
+    assert np.array_equal(same["mask"], keep_all["mask"]) and np.array_equal(same["cut_len"], keep_all["cut_len"])

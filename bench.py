@@ -61,6 +61,8 @@ def parse_args():
                     help="rollouts with advantage exactly 0 keep nothing (exact when the loss has no KL term)")
     ap.add_argument("--seed", type=int, default=2000)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-single-thread-tokens", type=int, default=24,
+                    help="kept tokens of the single-thread oracle timing (about 0.3 s each at the 8B head)")
     ap.add_argument("--kl-beta", type=float, default=0.0,
                     help="weight of the KL term of the token loss (reference log-probs are synthetic); 0 = off")
     ap.add_argument("--entropy", action="store_true", help="also accumulate the per-token entropy in the sweep")
@@ -72,6 +74,12 @@ def parse_args():
     ap.add_argument("--prefix-pack", action="store_true",
                     help="also build the truncated batch (prompt + kept prefix) each step; prefix schemes only")
     ap.add_argument("--prompts", type=int, default=None, help="override the number of prompts (smaller batch)")
+    ap.add_argument("--ceilings", action="store_true",
+                    help="instead of the loss benchmark: the practical ceilings on this GPU (HBM copy, matrix cores "
+                         "with operands in registers, the vendor GEMM on the three contraction shapes of --workload)")
+    ap.add_argument("--chunk-tokens", type=int, default=0,
+                    help="cap the loss call's workspace so that it works in chunks of at most this many kept tokens "
+                         "(a multiple of 256; 0 = the library's recommended workspace)")
     ap.add_argument("--stress-select", type=int, default=0, metavar="LOG2_TOKENS",
                     help="instead of the loss benchmark: time nat_select / nat_compact alone on 2^LOG2_TOKENS tokens")
     return ap.parse_args()
@@ -115,9 +123,25 @@ def cpu_baseline(batch, old_logp, scheme_code, args, torch):
     out = ogrpo.loss_and_grads(hidden[k], W, ids[k], old[k], adv[c["kept_seq"]], c["kept_w"].astype(np.float64))
     dt = time.perf_counter() - t0
     threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    # the same oracle call on one thread, on the first kept tokens of the sample
+    from threadpoolctl import threadpool_limits
+    k1 = k[:max(1, min(len(k), args.cpu_single_thread_tokens))]
+    with threadpool_limits(limits=1):
+        t1 = time.perf_counter()
+        ogrpo.loss_and_grads(hidden[k1], W, ids[k1], old[k1], adv[c["kept_seq"][:len(k1)]],
+                             c["kept_w"][:len(k1)].astype(np.float64))
+        dt1 = time.perf_counter() - t1
+    try:
+        usable = len(os.sched_getaffinity(0))
+    except AttributeError:
+        usable = os.cpu_count()
     return dict(value=c["n_kept"] / dt, unit="kept tokens/s", cores=int(threads), kind="oracle",
                 sample=f"{'last' if args.drop_zero_adv else 'first'} {len(lens)} rollouts truncated to <= {max_len} tokens ({int(cu[-1])} tokens, "
                        f"{c['n_kept']} kept) at the full head shape, fp64 numpy, {dt:.1f} s",
+                nproc=int(os.cpu_count() or 0), usable_cpus=int(usable or 0), blas_threads=int(threads),
+                single_thread_value=len(k1) / dt1,
+                single_thread_sample=f"the first {len(k1)} kept tokens of that sample, loss and gradients only, "
+                                     f"BLAS limited to one thread, {dt1:.1f} s",
                 loss=out["loss"])
 
 
@@ -192,11 +216,73 @@ def stress_select(args):
                       "config": {"workload": f"2^{args.stress_select} tokens in {B} rollouts"}, **out}))
 
 
+def ceilings(args):
+    """What bounds the loss stage's kernels on this GPU, measured with kernels of known work: an HBM copy,
+    the matrix cores on operands held in registers (constant, then pseudo-random bits: the chip is power
+    limited, so the rate depends on the data), and the vendor's GEMM (torch.matmul) on the three
+    contraction shapes of the workload's head with one full token chunk.  The vendor GEMM is a stated
+    ceiling only: nothing on the product path calls it."""
+    import torch
+    import synth_inputs as si
+    import paper_2603_06619_amd as nat
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    nat.load_library()
+    cfg = si.WORKLOADS[args.workload]
+    H, V, chunk = cfg["H"], cfg["V"], 32768
+
+    def timed_ms(fn, reps, warm=1):
+        for _ in range(warm):
+            fn()
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(reps):
+            fn()
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / reps
+
+    out = {}
+    nbytes = 4 << 30
+    src = torch.empty(nbytes, dtype=torch.uint8, device=dev).random_(0, 255)
+    dst = torch.empty_like(src)
+    ms = timed_ms(lambda: nat.nat_probe_copy(dst, src, nbytes), 10)
+    out["hbm_copy"] = dict(bytes_each_way=nbytes, ms=ms, GBps=2.0 * nbytes / ms / 1e6, frac_of_8TBps=2.0 * nbytes / ms / 1e6 / 8000.0)
+    del src, dst
+    scratch = torch.empty(nat.probe_mfma_scratch_bytes() // 4, dtype=torch.float32, device=dev)
+    for label, rnd in (("constant_operands", 0), ("random_operands", 1)):
+        flops = [0.0]
+        def launch():
+            flops[0] = nat.nat_probe_mfma_bf16(rnd, 40000, scratch)
+        ms = timed_ms(launch, 6)                      # ~70 ms per launch, ~0.4 s sustained
+        out["mfma_only_" + label] = dict(ms_per_launch=ms, TFLOPs=flops[0] / ms / 1e9,
+                                         frac_of_peak=flops[0] / ms / 1e9 / PEAK_BF16_TFLOPS)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(7)
+    rnd_bf16 = lambda r, c, std: (torch.randn((r, c), generator=gen, device=dev, dtype=torch.float32) * std).to(torch.bfloat16)
+    Wm, Hm = rnd_bf16(V, H, si.W_STD), rnd_bf16(chunk, H, 1.0)
+    E = rnd_bf16(chunk, V, 1.0).abs_()                 # soft-max numerators are positive
+    shapes = {"logits (W . H_chunk^T)": lambda: torch.matmul(Wm, Hm.t()),
+              "dH (E . W)": lambda: torch.matmul(E, Wm),
+              "dW (E^T . H_chunk)": lambda: torch.matmul(E.t(), Hm)}
+    vend = {}
+    for name, fn in shapes.items():
+        ms = timed_ms(fn, 8, warm=2)
+        vend[name] = dict(ms=ms, TFLOPs=2.0 * V * H * chunk / ms / 1e9, frac_of_peak=2.0 * V * H * chunk / ms / 1e9 / PEAK_BF16_TFLOPS)
+    out["vendor_gemm_bf16"] = vend
+    print(json.dumps({"metric": "practical ceilings for the loss stage's kernels", "n_gpus": 1, "data": "synthetic",
+                      "config": {"workload": args.workload, "H": H, "V": V, "chunk_tokens": chunk},
+                      "peak_bf16_TFLOPs": PEAK_BF16_TFLOPS, "peak_hbm_GBps": 8000.0, **out}))
+
+
 def main():
     args = parse_args()
+    if args.gpus != 1 and (args.stress_select or args.ceilings):
+        sys.exit(2)
+    if args.ceilings:
+        return ceilings(args)
     if args.stress_select:
-        if args.gpus != 1:
-            sys.exit(2)
         return stress_select(args)
     if args.gpus != 1:
         print(f"bench.py measures one GPU only (got --gpus {args.gpus}): no multi-GPU path is built; the stage "
@@ -227,8 +313,9 @@ def main():
     args.scheme_name = scheme_name
     batch = si.make_batch_torch(args.workload, args.seed, dev, P=args.prompts)
     P, G, B, N, H, V = batch["P"], batch["G"], batch["B"], batch["N"], batch["H"], batch["V"]
-    old_logp = si.behaviour_logp_stand_in(batch["hidden"], batch["W"], batch["ids"],
-                                          batch["logp_noise"] * args.logp_noise_scale)
+    # behaviour-policy log-probs: the current policy's (forward pass alone over every token) plus N(0, 0.05)
+    old_logp = stage.logp(batch["hidden"], batch["W"], batch["ids"], N)["logp"][:N] + batch["logp_noise"] * args.logp_noise_scale
+    torch.cuda.synchronize()
     rewards = torch.from_numpy(batch["rewards"].reshape(-1)).to(dev)
     cu = torch.from_numpy(batch["cu_seqlens"]).to(dev)
     spr = None
@@ -266,8 +353,11 @@ def main():
             # reference log-probs: the behaviour log-probs stand in (only their shape matters for the timing)
             kl = dict(ref_logp_k=sc["old_logp_k"], beta_kl=args.kl_beta, kl_kind=nat.KL_NONNEG,
                       want_kl=args.kl_beta > 0, want_entropy=args.entropy)
+        ws_bytes = None
+        if args.chunk_tokens:
+            ws_bytes = nat.loss_workspace_bytes(args.chunk_tokens, H, V, dtype_code) + 4 * max(nk, 1) + 4096
         out = stage.loss(sc["hidden_k"], batch["W"], sc["ids_k"], sc["old_logp_k"], adv, sc["kept_seq"], sc["kept_w"],
-                         nk, dW=dW, want_logp=True, **kl)
+                         nk, dW=dW, want_logp=True, ws_bytes=ws_bytes, **kl)
         return nk, out
 
     for w in range(args.warmup):
@@ -322,7 +412,9 @@ def main():
                    "p": args.p if scheme_name == "urs" else None, "min_cut": args.min_cut if scheme_name == "rpc" else None,
                    "kl_beta": args.kl_beta, "entropy": bool(args.entropy),
                    "drop_zero_adv": bool(args.drop_zero_adv),
-                   "forward_only": bool(args.forward_only), "logp_noise_scale": args.logp_noise_scale},
+                   "forward_only": bool(args.forward_only), "logp_noise_scale": args.logp_noise_scale,
+                   "chunk_tokens": args.chunk_tokens or None,
+                   "loss_workspace_gb": (nat.loss_workspace_bytes(args.chunk_tokens or int(kept_total / args.steps), H, V, dtype_code) / 1e9)},
         "mfma_util_pct_useful_6VH": 100.0 * useful_tflops / PEAK_BF16_TFLOPS,
         "mfma_util_pct_gemm_kernels_only": (100.0 * 2.0 * n_gemms * V * H * kept_total / (gemm_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS
                                             if gemm_ms > 0 else None),

@@ -26,7 +26,13 @@
  *     the host;
  *   - outputs are fully overwritten unless stated otherwise;
  *   - every function returns a nat_status and never throws; argument errors
- *     are detected on the host before anything is launched.
+ *     are detected on the host before anything is launched;
+ *   - values that live in device memory cannot be checked by the host.  The
+ *     kernels bound every access they derive from them: packed positions at or
+ *     beyond cu_seqlens[B] (when the host-passed N is larger) are never kept,
+ *     offsets beyond N are clamped to N, the kept-token outputs are written only
+ *     below their stated capacity, and token ids outside [0, V) are skipped and
+ *     counted (see nat_loss_fwd_bwd_kl).
  */
 #ifndef NAT_H_
 #define NAT_H_
@@ -53,6 +59,9 @@ enum { NAT_DTYPE_F32 = 0, NAT_DTYPE_BF16 = 1 };
 /* sampled-token forms of the KL term of Eq. 4, with d = ref_logp - logp:
  * LOG_RATIO: -d (the form named in the footnote to Eq. 4);  NONNEG: exp(d) - d - 1. */
 enum { NAT_KL_LOG_RATIO = 0, NAT_KL_NONNEG = 1 };
+/* words of the optional diagnostic array of nat_loss_fwd_bwd_kl / nat_logp_fwd */
+enum { NAT_DIAG_BAD_ID = 0, NAT_DIAG_SHIFT_RANGE = 1, NAT_DIAG_CLIPPED = 2, NAT_DIAG_NONZERO_ADV = 3,
+       NAT_DIAG_WORDS = 4 };
 
 /* Human-readable name of a status code (static string, never NULL). */
 const char* nat_status_string(nat_status s);
@@ -125,23 +134,27 @@ size_t nat_compact_workspace_bytes(int64_t N);
  * kept token (Eq. 6 / Eq. 9 folded with the 1/G * 1/|o_i| averaging of Eq. 5):
  *     kept_w = 1 / (n_rollouts_global * T_i * p_{i,t})   (one fp64 division, rounded to fp32)
  * with p_{i,t} recomputed from (scheme, p, C, T_i, t) of `params`.
- *   d_kept_idx [cap] int32 out: packed positions of kept tokens, ascending;
- *   d_kept_seq [cap] int32 out: rollout index i of each kept token;
- *   d_kept_w   [cap] float out;      cap >= number of kept tokens (N always suffices);
+ *   kept_cap   capacity, in kept tokens, of every per-kept-token output below (N always
+ *              suffices; a caller that knows a tighter bound may pass less).  Entries at
+ *              index >= kept_cap are not written; d_n_kept still reports the true count,
+ *              so n_kept > kept_cap tells the caller that the outputs are truncated;
+ *   d_kept_idx [kept_cap] int32 out: packed positions of kept tokens, ascending;
+ *   d_kept_seq [kept_cap] int32 out: rollout index i of each kept token;
+ *   d_kept_w   [kept_cap] float out;
  *   d_cu_kept  [B+1] int32 out: kept-token offsets per rollout;
  *   d_n_kept   [1] int32 out;  h_n_kept: optional PINNED host int32 that receives the
  *              same value by an asynchronous copy on `stream` (NULL = skip);
  *   optional gather (any of the three pairs may be NULL):
- *     d_hidden [N, H] -> d_hidden_k [cap, H] rows of kept tokens, dtype NAT_DTYPE_*,
- *     d_ids [N] -> d_ids_k [cap],  d_old_logp [N] -> d_old_logp_k [cap];
+ *     d_hidden [N, H] -> d_hidden_k [kept_cap, H] rows of kept tokens, dtype NAT_DTYPE_*,
+ *     d_ids [N] -> d_ids_k [kept_cap],  d_old_logp [N] -> d_old_logp_k [kept_cap];
  *   d_ws / ws_bytes: workspace of at least nat_compact_workspace_bytes(N).
- * Errors: as nat_select, plus n_rollouts_global <= 0, H <= 0 or a row size that is not
- * a multiple of 16 bytes when gathering -> NAT_BAD_SHAPE, d_hidden / d_hidden_k not 16-byte
- * aligned -> NAT_INVALID_ARG, workspace too small.
+ * Errors: as nat_select, plus n_rollouts_global <= 0, kept_cap < 0 -> NAT_INVALID_ARG; H <= 0
+ * or a row size that is not a multiple of 16 bytes when gathering -> NAT_BAD_SHAPE, d_hidden /
+ * d_hidden_k not 16-byte aligned -> NAT_INVALID_ARG, workspace too small.
  */
 nat_status nat_compact(const nat_select_params* params, int32_t n_rollouts_global,
                        const uint32_t* d_mask_bits, const int64_t* d_cu_seqlens, int32_t B, int64_t N,
-                       int32_t* d_kept_idx, int32_t* d_kept_seq, float* d_kept_w, int32_t* d_cu_kept,
+                       int64_t kept_cap, int32_t* d_kept_idx, int32_t* d_kept_seq, float* d_kept_w, int32_t* d_cu_kept,
                        int32_t* d_n_kept, int32_t* h_n_kept,
                        const void* d_hidden, void* d_hidden_k, int32_t H, int32_t dtype,
                        const int32_t* d_ids, int32_t* d_ids_k,
@@ -159,8 +172,12 @@ nat_status nat_compact(const nat_select_params* params, int32_t n_rollouts_globa
  *   from two words of one Philox block (stream 2) keyed by (seed, step, global rollout
  *   id); only seed, step and rollout_id_base of `params` are read.
  *   d_cut_len [B] int32 out: L_i;  d_mask_bits as in nat_select;
- *   d_pi      [N] double out: p_{i,t} = (sum_{l >= t} a_{i,l}) / A_i (one fp64 division of
- *             exact integers) for EVERY position, kept or not.
+ *   d_pi      [N] double out: p_{i,t} = (sum_{l >= t} a_{i,l}) / A_i for EVERY position, kept
+ *             or not: one fp64 division of the two integers, each converted to fp64 with
+ *             round-to-nearest-even.  Both are exact while A_i < 2^53 (any rollout shorter
+ *             than 2^21 tokens); beyond that (A_i can reach 2^63) each carries a relative
+ *             rounding error of at most 2^-53 before the division.  The cut itself is
+ *             always drawn in exact 64-bit integer arithmetic.
  * Errors: NULL pointer, B <= 0, N < 0 or N >= 2^31 -> NAT_INVALID_ARG.
  */
 nat_status nat_select_schedule(const nat_select_params* params, const uint32_t* d_weights,
@@ -190,7 +207,7 @@ nat_status nat_select_poisson(const nat_select_params* params, const double* d_p
  */
 nat_status nat_compact_pi(int32_t n_rollouts_global, const uint32_t* d_mask_bits, const double* d_pi,
                           const int64_t* d_cu_seqlens, int32_t B, int64_t N,
-                          int32_t* d_kept_idx, int32_t* d_kept_seq, float* d_kept_w, int32_t* d_cu_kept,
+                          int64_t kept_cap, int32_t* d_kept_idx, int32_t* d_kept_seq, float* d_kept_w, int32_t* d_cu_kept,
                           int32_t* d_n_kept, int32_t* h_n_kept,
                           const void* d_hidden, void* d_hidden_k, int32_t H, int32_t dtype,
                           const int32_t* d_ids, int32_t* d_ids_k,
@@ -198,9 +215,9 @@ nat_status nat_compact_pi(int32_t n_rollouts_global, const uint32_t* d_mask_bits
                           void* d_ws, size_t ws_bytes, void* stream);
 
 /*
- * Truncated batch for a model body that runs only over the kept prefixes (Sec. 4,
- * "prefix structure enables true forward truncation"): rollout i becomes its P_i prompt
- * tokens followed by its first L_i response tokens.
+ * Truncated batch for a model body that runs only over the kept prefixes (Sec. 4, the
+ * paragraph on compute savings): rollout i becomes its P_i prompt tokens followed by its
+ * first L_i response tokens.
  *   d_prompt_len [B] int32 or NULL (no prompts: P_i = 0);
  *   d_cu_seqlens [B+1] int64 response-token offsets as in nat_select;
  *   d_cut_len    [B] int32 from nat_select / nat_select_schedule (values outside [0, T_i]
@@ -234,23 +251,28 @@ nat_status nat_prefix_pack(const int32_t* d_prompt_len, const int64_t* d_cu_seql
 
 /*
  * Forward pass alone: log-probability of given tokens under the head (the evaluation that
- * produces behaviour and reference log-probs, Sec. 2 "forward pass of the current policy to
- * compute token log-probabilities"), and optionally the entropy of each row:
+ * produces behaviour and reference log-probs; Sec. 2, cost structure of a GRPO step, stage 2),
+ * and optionally the entropy of each row:
  *     z_k = W h_k,  logp_k = z_k[ids_k] - logsumexp(z_k),  entropy_k = -sum_v p_v log p_v.
  * Same projection kernel and the same arithmetic as nat_loss_fwd_bwd (identical log-probs for
  * identical chunking), but no soft-max numerators are written: 2 V H flops per token.
  *   d_hidden_k [N_k, H], d_W [V, H] row-major (bf16 or f32), d_ids_k [N_k] int32 in [0, V);
  *   d_logp_k [N_k] float out;  d_entropy_k [N_k] float out or NULL;
+ *   d_diag   [NAT_DIAG_WORDS] int32 out or NULL: NAT_DIAG_BAD_ID and NAT_DIAG_SHIFT_RANGE as
+ *            described at nat_loss_fwd_bwd_kl (the other words are set to 0); a token whose id
+ *            lies outside [0, V) gets log-prob NaN;
  *   d_ws / ws_bytes: at least nat_logp_workspace_min_bytes (nat_logp_workspace_bytes recommended).
  * The bf16 path shifts exponents by the target logit: as for nat_loss_fwd_bwd, log(p_max/p_target)
- * must stay below 70.  N_k = 0 is valid and does nothing.
+ * must stay below 70 (tokens beyond it are counted in d_diag).  N_k = 0 is valid and does nothing
+ * but clear d_diag.
  * Errors and alignment: as nat_loss_fwd_bwd.
  */
 size_t nat_logp_workspace_bytes(int32_t N_k, int32_t H, int32_t V, int32_t dtype);
 size_t nat_logp_workspace_min_bytes(int32_t N_k, int32_t H, int32_t V, int32_t dtype);
 nat_status nat_logp_fwd(const void* d_hidden_k, const void* d_W, const int32_t* d_ids_k,
                         int32_t N_k, int32_t H, int32_t V, int32_t dtype,
-                        float* d_logp_k, float* d_entropy_k, void* d_ws, size_t ws_bytes, void* stream);
+                        float* d_logp_k, float* d_entropy_k, int32_t* d_diag,
+                        void* d_ws, size_t ws_bytes, void* stream);
 
 /*
  * Workspace for nat_loss_fwd_bwd.  *_bytes is the recommended size (largest
@@ -280,7 +302,9 @@ size_t nat_loss_workspace_min_bytes(int32_t N_k, int32_t H, int32_t V, int32_t d
  *   The [N_k, V] logits are never written to memory as a whole; the bf16 path keeps the bf16
  *   soft-max numerators exp(z - z_target) of one token chunk (at most 32768 tokens) in the
  *   workspace.  That shift requires log(p_max / p_target) < 70 for every kept token (larger
- *   numerators are clamped); the fp32 path has no such bound.
+ *   numerators are clamped; nat_loss_fwd_bwd_kl counts the tokens this may have touched); the
+ *   fp32 path has no such bound.  A token whose id lies outside [0, V) is left out of loss, dH
+ *   and dW (nat_loss_fwd_bwd_kl counts those too).
  * N_k = 0 is valid: loss = 0, d_dW zeroed unless accumulating, d_dH_k untouched.
  *   Alignment: d_hidden_k, d_W, d_dH_k, d_dW 16 bytes; d_ws 256 bytes (else NAT_INVALID_ARG).
  * Errors: NULL pointer, N_k < 0, eps < 0 -> NAT_INVALID_ARG; H <= 0, V <= 0, or (bf16) H not
@@ -307,6 +331,22 @@ nat_status nat_loss_fwd_bwd(const void* d_hidden_k, const void* d_W, const int32
  *   d_entropy_k  [N_k] float out or NULL: -sum_v p_v log p_v of the current policy at each
  *                kept token (the quantity of the paper's entropy curves), accumulated in the
  *                same sweep over the vocabulary; it has no gradient.
+ *   d_diag       [NAT_DIAG_WORDS] int32 out or NULL: counters over the kept tokens of this call
+ *                (cleared first, exact, independent of scheduling):
+ *                  NAT_DIAG_BAD_ID       tokens whose id lies outside [0, V).  Such a token is
+ *                                        left out: no contribution to loss, dH (its row is 0) or
+ *                                        dW; its log-prob and KL are reported as NaN;
+ *                  NAT_DIAG_SHIFT_RANGE  (bf16 path) tokens for which some 128-row block of the
+ *                                        vocabulary has numerators summing to e^70 or more, i.e.
+ *                                        log(p_max / p_target) reached the range where the clamp
+ *                                        of the exponent shift may have acted: their log-probs
+ *                                        and gradients are not reliable.  Always 0 on the fp32
+ *                                        path, which shifts by the row maximum;
+ *                  NAT_DIAG_CLIPPED      tokens with A != 0 whose surrogate gradient is zero
+ *                                        because the ratio left [1 - eps_lo, 1 + eps_hi] on the
+ *                                        side that Eq. 3 clips (the clipping frequency of the
+ *                                        paper's App. C figure is CLIPPED / NONZERO_ADV);
+ *                  NAT_DIAG_NONZERO_ADV  tokens with A != 0.
  * Errors: as nat_loss_fwd_bwd, plus beta_kl < 0, unknown kl_kind, or beta_kl > 0 with
  * d_ref_logp_k NULL -> NAT_INVALID_ARG.
  */
@@ -316,7 +356,7 @@ nat_status nat_loss_fwd_bwd_kl(const void* d_hidden_k, const void* d_W, const in
                                float eps_lo, float eps_hi, float grad_scale,
                                const float* d_ref_logp_k, float beta_kl, int32_t kl_kind,
                                float* d_loss, float* d_logp_k, float* d_kl_k, float* d_entropy_k,
-                               void* d_dH_k, float* d_dW, int32_t accumulate_dw,
+                               int32_t* d_diag, void* d_dH_k, float* d_dW, int32_t accumulate_dw,
                                void* d_ws, size_t ws_bytes, void* stream);
 
 /*
@@ -330,6 +370,23 @@ int32_t nat_profile_num_classes(void);
 const char* nat_profile_class_name(int32_t cls);
 nat_status nat_profile_enable(int32_t on);
 nat_status nat_profile_collect(double* h_ms, int64_t* h_launches, int32_t n_classes);
+
+/*
+ * Practical ceilings of the machine (measurement aids, not on the path).  The caller times them
+ * with events on `stream`.
+ *   nat_probe_mfma_bf16: 2048 workgroups of 4 wavefronts, each issuing `iters` x 16 independent
+ *     32x32x16 bf16 matrix products on operands held in registers (random_operands = 0: constant
+ *     operands; 1: pseudo-random sign and mantissa bits, which is what the power limit sees on
+ *     real data).  d_scratch: nat_probe_mfma_scratch_bytes() of device memory (written, contents
+ *     meaningless); *h_flops (HOST, may be NULL) receives the flops of the launch.
+ *   nat_probe_copy: copies `bytes` (a multiple of 16; both pointers 16-byte aligned) with 16-byte
+ *     loads and stores: 2 * bytes of HBM traffic of known size.
+ * Errors: NULL pointer, iters <= 0, misaligned or odd-sized copy -> NAT_INVALID_ARG.
+ */
+size_t nat_probe_mfma_scratch_bytes(void);
+nat_status nat_probe_mfma_bf16(int32_t random_operands, int32_t iters, float* d_scratch,
+                               double* h_flops, void* stream);
+nat_status nat_probe_copy(void* d_dst, const void* d_src, size_t bytes, void* stream);
 
 #ifdef __cplusplus
 }

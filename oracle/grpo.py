@@ -109,7 +109,7 @@ def loss_and_grads(hidden, W, ids, old_logp, adv_tok, w, eps_lo=0.2, eps_hi=0.2,
     c_k = -grad_scale * w_k * (dS_k/dlogp_k - beta_kl * dKL_k/dlogp_k) ;
     dH = dlogits W ;  dW = dlogits^T H.
     Returns dict(loss, logp [n], dH [n, H], dW [V, H], S [n], r [n], kl [n],
-    entropy [n]).
+    entropy [n], c [n]).
     """
     Hm = np.asarray(hidden, dtype=np.float64)
     Wd = np.asarray(W, dtype=np.float64)
@@ -118,7 +118,7 @@ def loss_and_grads(hidden, W, ids, old_logp, adv_tok, w, eps_lo=0.2, eps_hi=0.2,
     n = Hm.shape[0]
     if n == 0:
         return dict(loss=0.0, logp=np.zeros(0), dH=np.zeros_like(Hm), dW=np.zeros_like(Wd),
-                    S=np.zeros(0), r=np.zeros(0), kl=np.zeros(0), entropy=np.zeros(0))
+                    S=np.zeros(0), r=np.zeros(0), kl=np.zeros(0), entropy=np.zeros(0), c=np.zeros(0))
     logpi = log_softmax_rows(Hm @ Wd.T)            # [n, V]
     rows = np.arange(n)
     logp = logpi[rows, ids]
@@ -132,7 +132,7 @@ def loss_and_grads(hidden, W, ids, old_logp, adv_tok, w, eps_lo=0.2, eps_hi=0.2,
     dZ[rows, ids] += c                              # + c * onehot
     dH = dZ @ Wd
     dW = dZ.T @ Hm
-    return dict(loss=loss, logp=logp, dH=dH, dW=dW, S=S, r=r, kl=kl, entropy=entropy_rows(logpi))
+    return dict(loss=loss, logp=logp, dH=dH, dW=dW, S=S, r=r, kl=kl, entropy=entropy_rows(logpi), c=c)
 
 
 def objective_value(hidden, W, ids, old_logp, adv_tok, w, eps_lo=0.2, eps_hi=0.2,

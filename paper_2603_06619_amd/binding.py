@@ -11,6 +11,7 @@ _lib = None
 FULL, URS, RPC, DET = 0, 1, 2, 3
 DTYPE_F32, DTYPE_BF16 = 0, 1
 KL_LOG_RATIO, KL_NONNEG = 0, 1
+DIAG_BAD_ID, DIAG_SHIFT_RANGE, DIAG_CLIPPED, DIAG_NONZERO_ADV, DIAG_WORDS = 0, 1, 2, 3, 4
 
 
 class NatError(RuntimeError):
@@ -74,14 +75,14 @@ def load_library():
     lib.nat_compact_workspace_bytes.restype = sz
     lib.nat_compact_workspace_bytes.argtypes = [i64]
     lib.nat_compact.restype = i32
-    lib.nat_compact.argtypes = [pp, i32, vp, vp, i32, i64, vp, vp, vp, vp, vp, vp, vp, vp, i32, i32,
+    lib.nat_compact.argtypes = [pp, i32, vp, vp, i32, i64, i64, vp, vp, vp, vp, vp, vp, vp, vp, i32, i32,
                                 vp, vp, vp, vp, vp, sz, vp]
     lib.nat_select_schedule.restype = i32
     lib.nat_select_schedule.argtypes = [pp, vp, vp, i32, i64, vp, vp, vp, vp]
     lib.nat_select_poisson.restype = i32
     lib.nat_select_poisson.argtypes = [pp, vp, vp, i32, i64, vp, vp]
     lib.nat_compact_pi.restype = i32
-    lib.nat_compact_pi.argtypes = [i32, vp, vp, vp, i32, i64, vp, vp, vp, vp, vp, vp, vp, vp, i32, i32,
+    lib.nat_compact_pi.argtypes = [i32, vp, vp, vp, i32, i64, i64, vp, vp, vp, vp, vp, vp, vp, vp, i32, i32,
                                    vp, vp, vp, vp, vp, sz, vp]
     lib.nat_prefix_pack.restype = i32
     lib.nat_prefix_pack.argtypes = [vp, vp, vp, i32, i32, i64, i64, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
@@ -93,12 +94,18 @@ def load_library():
                                      vp, vp, vp, vp, i32, vp, sz, vp]
     lib.nat_loss_fwd_bwd_kl.restype = i32
     lib.nat_loss_fwd_bwd_kl.argtypes = [vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, f32, f32, f32,
-                                        vp, f32, i32, vp, vp, vp, vp, vp, vp, i32, vp, sz, vp]
+                                        vp, f32, i32, vp, vp, vp, vp, vp, vp, vp, i32, vp, sz, vp]
     for name in ("nat_logp_workspace_bytes", "nat_logp_workspace_min_bytes"):
         getattr(lib, name).restype = sz
         getattr(lib, name).argtypes = [i32, i32, i32, i32]
     lib.nat_logp_fwd.restype = i32
-    lib.nat_logp_fwd.argtypes = [vp, vp, vp, i32, i32, i32, i32, vp, vp, vp, sz, vp]
+    lib.nat_logp_fwd.argtypes = [vp, vp, vp, i32, i32, i32, i32, vp, vp, vp, vp, sz, vp]
+    lib.nat_probe_mfma_scratch_bytes.restype = sz
+    lib.nat_probe_mfma_scratch_bytes.argtypes = []
+    lib.nat_probe_mfma_bf16.restype = i32
+    lib.nat_probe_mfma_bf16.argtypes = [i32, i32, vp, ctypes.POINTER(ctypes.c_double), vp]
+    lib.nat_probe_copy.restype = i32
+    lib.nat_probe_copy.argtypes = [vp, vp, sz, vp]
     lib.nat_profile_num_classes.restype = i32
     lib.nat_profile_class_name.restype = ctypes.c_char_p
     lib.nat_profile_class_name.argtypes = [i32]
@@ -172,14 +179,20 @@ def nat_select(params, cu_seqlens, B, N, cut_len_out, mask_bits_out):
                                      _ptr(mask_bits_out), _stream()), "nat_select")
 
 
+def _kept_cap(kept_cap, kept_idx):
+    return int(kept_idx.numel() if kept_cap is None and kept_idx is not None else (kept_cap or 0))
+
+
 def nat_compact(params, n_rollouts_global, mask_bits, cu_seqlens, B, N, kept_idx, kept_seq, kept_w, cu_kept,
                 n_kept, h_n_kept, workspace, hidden=None, hidden_k=None, ids=None, ids_k=None,
-                old_logp=None, old_logp_k=None):
+                old_logp=None, old_logp_k=None, kept_cap=None):
+    """kept_cap: capacity of the per-kept-token outputs; default: the length of kept_idx."""
     c = params._c()
     H = hidden.shape[1] if hidden is not None else 0
     dt = _dtype_code(hidden) if hidden is not None else DTYPE_F32
     _raise(load_library().nat_compact(
-        ctypes.byref(c), n_rollouts_global, _ptr(mask_bits), _ptr(cu_seqlens), B, N, _ptr(kept_idx), _ptr(kept_seq),
+        ctypes.byref(c), n_rollouts_global, _ptr(mask_bits), _ptr(cu_seqlens), B, N, _kept_cap(kept_cap, kept_idx),
+        _ptr(kept_idx), _ptr(kept_seq),
         _ptr(kept_w), _ptr(cu_kept), _ptr(n_kept), _ptr(h_n_kept), _ptr(hidden), _ptr(hidden_k), H, dt,
         _ptr(ids), _ptr(ids_k), _ptr(old_logp), _ptr(old_logp_k), _ptr(workspace),
         workspace.numel() * workspace.element_size() if workspace is not None else 0, _stream()), "nat_compact")
@@ -208,12 +221,13 @@ def nat_select_poisson(params, pi, cu_seqlens, B, N, mask_bits_out):
 
 def nat_compact_pi(n_rollouts_global, mask_bits, pi, cu_seqlens, B, N, kept_idx, kept_seq, kept_w, cu_kept,
                    n_kept, h_n_kept, workspace, hidden=None, hidden_k=None, ids=None, ids_k=None,
-                   old_logp=None, old_logp_k=None):
+                   old_logp=None, old_logp_k=None, kept_cap=None):
     _check(pi, torch.float64, "pi")
     H = hidden.shape[1] if hidden is not None else 0
     dt = _dtype_code(hidden) if hidden is not None else DTYPE_F32
     _raise(load_library().nat_compact_pi(
-        n_rollouts_global, _ptr(mask_bits), _ptr(pi), _ptr(cu_seqlens), B, N, _ptr(kept_idx), _ptr(kept_seq),
+        n_rollouts_global, _ptr(mask_bits), _ptr(pi), _ptr(cu_seqlens), B, N, _kept_cap(kept_cap, kept_idx),
+        _ptr(kept_idx), _ptr(kept_seq),
         _ptr(kept_w), _ptr(cu_kept), _ptr(n_kept), _ptr(h_n_kept), _ptr(hidden), _ptr(hidden_k), H, dt,
         _ptr(ids), _ptr(ids_k), _ptr(old_logp), _ptr(old_logp_k), _ptr(workspace),
         workspace.numel() * workspace.element_size() if workspace is not None else 0, _stream()), "nat_compact_pi")
@@ -241,12 +255,12 @@ def nat_loss_fwd_bwd(hidden_k, W, ids_k, old_logp_k, adv, kept_seq, kept_w, N_k,
 
 def nat_loss_fwd_bwd_kl(hidden_k, W, ids_k, old_logp_k, adv, kept_seq, kept_w, N_k, eps_lo, eps_hi, grad_scale,
                         ref_logp_k, beta_kl, kl_kind, loss_out, logp_out, kl_out, entropy_out, dH_out, dW_out,
-                        accumulate_dw, workspace):
+                        accumulate_dw, workspace, diag_out=None):
     V, H = W.shape
     _raise(load_library().nat_loss_fwd_bwd_kl(
         _ptr(hidden_k), _ptr(W), _ptr(ids_k), _ptr(old_logp_k), _ptr(adv), _ptr(kept_seq), _ptr(kept_w),
         N_k, H, V, _dtype_code(W), eps_lo, eps_hi, grad_scale, _ptr(ref_logp_k), float(beta_kl), int(kl_kind),
-        _ptr(loss_out), _ptr(logp_out), _ptr(kl_out), _ptr(entropy_out), _ptr(dH_out), _ptr(dW_out),
+        _ptr(loss_out), _ptr(logp_out), _ptr(kl_out), _ptr(entropy_out), _ptr(diag_out), _ptr(dH_out), _ptr(dW_out),
         int(accumulate_dw), _ptr(workspace),
         workspace.numel() * workspace.element_size() if workspace is not None else 0, _stream()),
         "nat_loss_fwd_bwd_kl")
@@ -260,12 +274,28 @@ def logp_workspace_min_bytes(N_k, H, V, dtype):
     return int(load_library().nat_logp_workspace_min_bytes(int(N_k), int(H), int(V), int(dtype)))
 
 
-def nat_logp_fwd(hidden_k, W, ids_k, N_k, logp_out, entropy_out, workspace):
+def nat_logp_fwd(hidden_k, W, ids_k, N_k, logp_out, entropy_out, workspace, diag_out=None):
     V, H = W.shape
     _raise(load_library().nat_logp_fwd(
         _ptr(hidden_k), _ptr(W), _ptr(ids_k), N_k, H, V, _dtype_code(W), _ptr(logp_out), _ptr(entropy_out),
-        _ptr(workspace), workspace.numel() * workspace.element_size() if workspace is not None else 0, _stream()),
+        _ptr(diag_out), _ptr(workspace), workspace.numel() * workspace.element_size() if workspace is not None else 0, _stream()),
         "nat_logp_fwd")
+
+
+def probe_mfma_scratch_bytes():
+    return int(load_library().nat_probe_mfma_scratch_bytes())
+
+
+def nat_probe_mfma_bf16(random_operands, iters, scratch):
+    """Launches the matrix-core probe on the current stream; returns the flops of the launch."""
+    flops = ctypes.c_double(0.0)
+    _raise(load_library().nat_probe_mfma_bf16(int(bool(random_operands)), int(iters), _ptr(scratch),
+                                              ctypes.byref(flops), _stream()), "nat_probe_mfma_bf16")
+    return flops.value
+
+
+def nat_probe_copy(dst, src, nbytes):
+    _raise(load_library().nat_probe_copy(_ptr(dst), _ptr(src), int(nbytes), _stream()), "nat_probe_copy")
 
 
 def profile_enable(on):

@@ -7,7 +7,7 @@ PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG_DIR)
 CSRC = os.path.join(PKG_DIR, "csrc")
 LIB_PATH = os.path.join(PKG_DIR, "libnat_hip.so")
-SOURCES = ["api.hip", "select.hip", "compact.hip", "schedule.hip", "loss_f32.hip", "loss_bf16.hip"]
+SOURCES = ["api.hip", "select.hip", "compact.hip", "schedule.hip", "loss_f32.hip", "loss_bf16.hip", "ceilings.hip"]
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
     # keep packed-fp32 instruction selection off for all device code

@@ -17,7 +17,8 @@ const char* const kClassNames[PC_NUM] = {
     "dhidden_gemm", "dweight_gemm", "loss_reduce", "f32_path", "fill", "schedule", "prefix_pack"};
 }  // namespace
 
-ProfScope::ProfScope(int cls, hipStream_t s) : cls_(cls), s_(s), rec_(nullptr) {
+ProfScope::ProfScope(int cls, hipStream_t s, bool enabled) : cls_(cls), s_(s), rec_(nullptr) {
+  if (!enabled) return;
   std::lock_guard<std::mutex> lock(g_prof_mutex);
   if (!g_prof_on) return;
   EventPair* ep = new EventPair{nullptr, nullptr, cls};
@@ -135,18 +136,26 @@ extern "C" size_t nat_logp_workspace_min_bytes(int32_t N_k, int32_t H, int32_t V
   return 0;
 }
 
+// the diagnostic counters are integers: cleared through the float fill (all-zero bits)
+static nat_status clear_diag(int32_t* d_diag, hipStream_t s) {
+  return d_diag ? fill_zero_f32((float*)d_diag, NAT_DIAG_WORDS, s) : NAT_OK;
+}
+
 extern "C" nat_status nat_logp_fwd(const void* d_hidden_k, const void* d_W, const int32_t* d_ids_k,
                                    int32_t N_k, int32_t H, int32_t V, int32_t dtype,
-                                   float* d_logp_k, float* d_entropy_k, void* d_ws, size_t ws_bytes, void* stream) {
+                                   float* d_logp_k, float* d_entropy_k, int32_t* d_diag,
+                                   void* d_ws, size_t ws_bytes, void* stream) {
   if (dtype != NAT_DTYPE_F32 && dtype != NAT_DTYPE_BF16) return NAT_UNSUPPORTED_DTYPE;
   if (N_k < 0) return NAT_INVALID_ARG;
   if (H <= 0 || V <= 0) return NAT_BAD_SHAPE;
   if (dtype == NAT_DTYPE_BF16 && (H % 64) != 0) return NAT_BAD_SHAPE;
-  if (N_k == 0) return NAT_OK;
+  if (N_k == 0) return clear_diag(d_diag, (hipStream_t)stream);
   if (!d_hidden_k || !d_W || !d_ids_k || !d_logp_k) return NAT_INVALID_ARG;
   if (!d_ws || ws_bytes < nat_logp_workspace_min_bytes(N_k, H, V, dtype)) return NAT_WORKSPACE_TOO_SMALL;
   if (((uintptr_t)d_ws & 255) || ((uintptr_t)d_hidden_k & 15) || ((uintptr_t)d_W & 15)) return NAT_INVALID_ARG;
-  LogpArgs a{d_hidden_k, d_W, d_ids_k, N_k, H, V, d_logp_k, d_entropy_k, d_ws, ws_bytes, (hipStream_t)stream};
+  nat_status st = clear_diag(d_diag, (hipStream_t)stream);
+  if (st != NAT_OK) return st;
+  LogpArgs a{d_hidden_k, d_W, d_ids_k, N_k, H, V, d_logp_k, d_entropy_k, d_ws, ws_bytes, (hipStream_t)stream, d_diag};
   return dtype == NAT_DTYPE_BF16 ? logp_bf16_run(a) : logp_f32_run(a);
 }
 
@@ -156,7 +165,7 @@ extern "C" nat_status nat_loss_fwd_bwd_kl(const void* d_hidden_k, const void* d_
                                           float eps_lo, float eps_hi, float grad_scale,
                                           const float* d_ref_logp_k, float beta_kl, int32_t kl_kind,
                                           float* d_loss, float* d_logp_k, float* d_kl_k, float* d_entropy_k,
-                                          void* d_dH_k, float* d_dW, int32_t accumulate_dw,
+                                          int32_t* d_diag, void* d_dH_k, float* d_dW, int32_t accumulate_dw,
                                           void* d_ws, size_t ws_bytes, void* stream) {
   if (dtype != NAT_DTYPE_F32 && dtype != NAT_DTYPE_BF16) return NAT_UNSUPPORTED_DTYPE;
   if (N_k < 0 || !(eps_lo >= 0.f) || !(eps_hi >= 0.f) || !(beta_kl >= 0.f)) return NAT_INVALID_ARG;
@@ -171,6 +180,8 @@ extern "C" nat_status nat_loss_fwd_bwd_kl(const void* d_hidden_k, const void* d_
   if (N_k == 0) {
     nat_status st = fill_zero_f32(d_loss, 1, s);
     if (st != NAT_OK) return st;
+    st = clear_diag(d_diag, s);
+    if (st != NAT_OK) return st;
     return accumulate_dw ? NAT_OK : fill_zero_f32(d_dW, (size_t)V * (size_t)H, s);
   }
   if (!d_ws || ws_bytes < nat_loss_workspace_min_bytes(N_k, H, V, dtype)) return NAT_WORKSPACE_TOO_SMALL;
@@ -178,9 +189,11 @@ extern "C" nat_status nat_loss_fwd_bwd_kl(const void* d_hidden_k, const void* d_
   if (((uintptr_t)d_ws & 255) || ((uintptr_t)d_hidden_k & 15) || ((uintptr_t)d_W & 15) || ((uintptr_t)d_dH_k & 15) ||
       ((uintptr_t)d_dW & 15))
     return NAT_INVALID_ARG;
+  nat_status st_diag = clear_diag(d_diag, s);
+  if (st_diag != NAT_OK) return st_diag;
   LossArgs a{d_hidden_k, d_W, d_ids_k, d_old_logp_k, d_adv, d_kept_seq, d_kept_w, N_k, H, V,
              eps_lo, eps_hi, grad_scale, d_loss, d_logp_k, d_dH_k, d_dW, accumulate_dw, d_ws, ws_bytes, s,
-             d_ref_logp_k, beta_kl, kl_kind, d_kl_k, d_entropy_k};
+             d_ref_logp_k, beta_kl, kl_kind, d_kl_k, d_entropy_k, d_diag};
   return dtype == NAT_DTYPE_BF16 ? loss_bf16_run(a) : loss_f32_run(a);
 }
 
@@ -192,5 +205,5 @@ extern "C" nat_status nat_loss_fwd_bwd(const void* d_hidden_k, const void* d_W, 
                                        int32_t accumulate_dw, void* d_ws, size_t ws_bytes, void* stream) {
   return nat_loss_fwd_bwd_kl(d_hidden_k, d_W, d_ids_k, d_old_logp_k, d_adv, d_kept_seq, d_kept_w, N_k, H, V, dtype,
                              eps_lo, eps_hi, grad_scale, nullptr, 0.f, NAT_KL_LOG_RATIO, d_loss, d_logp_k, nullptr,
-                             nullptr, d_dH_k, d_dW, accumulate_dw, d_ws, ws_bytes, stream);
+                             nullptr, nullptr, d_dH_k, d_dW, accumulate_dw, d_ws, ws_bytes, stream);
 }

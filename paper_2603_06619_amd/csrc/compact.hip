@@ -82,7 +82,7 @@ __device__ __forceinline__ float ht_weight(int scheme, int64_t T, int64_t t, dou
 
 __global__ void __launch_bounds__(kScatterThreads)
 compact_scatter_kernel(SelectArgs a, double n_rollouts, const double* __restrict__ pi,
-                       const uint32_t* __restrict__ mask_bits, int64_t n_words,
+                       const uint32_t* __restrict__ mask_bits, int64_t n_words, int64_t n_tokens, int64_t kept_cap,
                        const int64_t* __restrict__ cu, int B, const int32_t* __restrict__ tile_offset,
                        int32_t* __restrict__ kept_idx, int32_t* __restrict__ kept_seq, float* __restrict__ kept_w) {
   __shared__ int wave_cnt[4];
@@ -112,8 +112,10 @@ compact_scatter_kernel(SelectArgs a, double n_rollouts, const double* __restrict
     if (group == 0) continue;                                   // wave-uniform
     const bool keep = (group >> lane) & 1ull;
     const int rank = __popcll(group & ((1ull << lane) - 1ull));
-    if (keep) {
-      const int64_t n = (word0 + 2 * it) * 32 + lane;
+    const int64_t n = (word0 + 2 * it) * 32 + lane;
+    // entries beyond the outputs' capacity are counted but not written; a set bit at a position the
+    // per-token arrays do not have (a foreign mask) is ranked but reads and writes nothing
+    if (keep && base + rank < kept_cap && n < n_tokens) {
       const int i = rollout_of_pos(cu, i_lo, i_hi, n);
       const int64_t start = cu[i];
       const int64_t T = cu[i + 1] - start;
@@ -130,10 +132,11 @@ compact_scatter_kernel(SelectArgs a, double n_rollouts, const double* __restrict
 
 // cu_kept[i] = number of kept tokens at packed positions < cu[i]
 __global__ void compact_cu_kept_kernel(const uint32_t* __restrict__ mask_bits, const int64_t* __restrict__ cu, int B,
-                                       const int32_t* __restrict__ tile_offset, int32_t* __restrict__ cu_kept) {
+                                       int64_t n_tokens, const int32_t* __restrict__ tile_offset,
+                                       int32_t* __restrict__ cu_kept) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i > B) return;
-  const int64_t pos = cu[i];
+  const int64_t pos = cu[i] < 0 ? 0 : cu[i] > n_tokens ? n_tokens : cu[i];   // the mask holds n_tokens positions
   const int64_t tile = pos / kTileTokens;
   int c = tile_offset[tile];
   const int64_t w0 = tile * kTileWords, w1 = pos >> 5;
@@ -181,9 +184,10 @@ namespace nat {
 
 nat_status compact_run(const SelectArgs& a, const CompactArgs& c) {
   if (!c.cu || !c.cu_kept || !c.n_kept || c.B <= 0 || c.N < 0 || c.N >= (int64_t(1) << 31) ||
-      c.n_rollouts_global <= 0)
+      c.n_rollouts_global <= 0 || c.kept_cap < 0)
     return NAT_INVALID_ARG;
-  if (c.N > 0 && (!c.mask_bits || !c.kept_idx || !c.kept_seq || !c.kept_w)) return NAT_INVALID_ARG;
+  if (c.N > 0 && !c.mask_bits) return NAT_INVALID_ARG;
+  if (c.N > 0 && c.kept_cap > 0 && (!c.kept_idx || !c.kept_seq || !c.kept_w)) return NAT_INVALID_ARG;
   if ((c.hidden != nullptr) != (c.hidden_k != nullptr) || (c.ids != nullptr) != (c.ids_k != nullptr) ||
       (c.old_logp != nullptr) != (c.old_logp_k != nullptr))
     return NAT_INVALID_ARG;
@@ -203,7 +207,7 @@ nat_status compact_run(const SelectArgs& a, const CompactArgs& c) {
   int32_t* tile_count = (int32_t*)c.ws;
   int32_t* tile_offset = tile_count + n_tiles;
   {
-    ProfScope prof(PC_COMPACT, s);
+    ProfScope prof(PC_COMPACT, s, !c.no_timing);
     if (n_tiles > 0) {
       compact_count_kernel<<<(unsigned)n_tiles, kTileWords, 0, s>>>(c.mask_bits, n_words, tile_count);
       NAT_LAUNCH_CHECK();
@@ -212,18 +216,19 @@ nat_status compact_run(const SelectArgs& a, const CompactArgs& c) {
     NAT_LAUNCH_CHECK();
     if (n_tiles > 0) {
       compact_scatter_kernel<<<(unsigned)n_tiles, kScatterThreads, 0, s>>>(
-          a, (double)c.n_rollouts_global, c.pi, c.mask_bits, n_words, c.cu, c.B, tile_offset,
+          a, (double)c.n_rollouts_global, c.pi, c.mask_bits, n_words, c.N, c.kept_cap, c.cu, c.B, tile_offset,
           c.kept_idx, c.kept_seq, c.kept_w);
       NAT_LAUNCH_CHECK();
     }
-    compact_cu_kept_kernel<<<(c.B + 1 + 255) / 256, 256, 0, s>>>(c.mask_bits, c.cu, c.B, tile_offset, c.cu_kept);
+    compact_cu_kept_kernel<<<(c.B + 1 + 255) / 256, 256, 0, s>>>(c.mask_bits, c.cu, c.B, c.N, tile_offset, c.cu_kept);
     NAT_LAUNCH_CHECK();
   }
   if (c.h_n_kept) NAT_HIP_TRY(hipMemcpyAsync(c.h_n_kept, c.n_kept, sizeof(int32_t), hipMemcpyDeviceToHost, s));
-  if (c.N > 0 && (c.hidden || c.ids || c.old_logp)) {
-    ProfScope prof(PC_GATHER, s);
-    const int64_t grid = c.N < 65536 * 4 ? c.N : 65536 * 4;
-    gather_rows_kernel<<<(unsigned)grid, 256, 0, s>>>(c.kept_idx, c.n_kept, c.N, (const uint4*)c.hidden,
+  const int64_t gather_rows = c.N < c.kept_cap ? c.N : c.kept_cap;
+  if (gather_rows > 0 && (c.hidden || c.ids || c.old_logp)) {
+    ProfScope prof(PC_GATHER, s, !c.no_timing);
+    const int64_t grid = gather_rows < 65536 * 4 ? gather_rows : 65536 * 4;
+    gather_rows_kernel<<<(unsigned)grid, 256, 0, s>>>(c.kept_idx, c.n_kept, gather_rows, (const uint4*)c.hidden,
                                                      (uint4*)c.hidden_k, row_bytes / 16, c.ids, c.ids_k,
                                                      c.old_logp, c.old_logp_k);
     NAT_LAUNCH_CHECK();
@@ -235,7 +240,7 @@ nat_status compact_run(const SelectArgs& a, const CompactArgs& c) {
 
 extern "C" nat_status nat_compact(const nat_select_params* params, int32_t n_rollouts_global,
                                   const uint32_t* d_mask_bits, const int64_t* d_cu_seqlens, int32_t B, int64_t N,
-                                  int32_t* d_kept_idx, int32_t* d_kept_seq, float* d_kept_w, int32_t* d_cu_kept,
+                                  int64_t kept_cap, int32_t* d_kept_idx, int32_t* d_kept_seq, float* d_kept_w, int32_t* d_cu_kept,
                                   int32_t* d_n_kept, int32_t* h_n_kept,
                                   const void* d_hidden, void* d_hidden_k, int32_t H, int32_t dtype,
                                   const int32_t* d_ids, int32_t* d_ids_k,
@@ -244,15 +249,15 @@ extern "C" nat_status nat_compact(const nat_select_params* params, int32_t n_rol
   SelectArgs a;
   nat_status st = validate_select(params, &a);
   if (st != NAT_OK) return st;
-  return compact_run(a, CompactArgs{n_rollouts_global, d_mask_bits, nullptr, d_cu_seqlens, B, N, d_kept_idx,
+  return compact_run(a, CompactArgs{n_rollouts_global, d_mask_bits, nullptr, d_cu_seqlens, B, N, kept_cap, d_kept_idx,
                                     d_kept_seq, d_kept_w, d_cu_kept, d_n_kept, h_n_kept, d_hidden, d_hidden_k, H,
                                     dtype, d_ids, d_ids_k, d_old_logp, d_old_logp_k, d_ws, ws_bytes,
-                                    (hipStream_t)stream});
+                                    (hipStream_t)stream, false});
 }
 
 extern "C" nat_status nat_compact_pi(int32_t n_rollouts_global, const uint32_t* d_mask_bits, const double* d_pi,
                                      const int64_t* d_cu_seqlens, int32_t B, int64_t N,
-                                     int32_t* d_kept_idx, int32_t* d_kept_seq, float* d_kept_w, int32_t* d_cu_kept,
+                                     int64_t kept_cap, int32_t* d_kept_idx, int32_t* d_kept_seq, float* d_kept_w, int32_t* d_cu_kept,
                                      int32_t* d_n_kept, int32_t* h_n_kept,
                                      const void* d_hidden, void* d_hidden_k, int32_t H, int32_t dtype,
                                      const int32_t* d_ids, int32_t* d_ids_k,
@@ -263,8 +268,8 @@ extern "C" nat_status nat_compact_pi(int32_t n_rollouts_global, const uint32_t* 
   a.scheme = NAT_SCHEME_FULL;
   a.min_cut = 1;
   a.p = 1.0;
-  return compact_run(a, CompactArgs{n_rollouts_global, d_mask_bits, d_pi, d_cu_seqlens, B, N, d_kept_idx,
+  return compact_run(a, CompactArgs{n_rollouts_global, d_mask_bits, d_pi, d_cu_seqlens, B, N, kept_cap, d_kept_idx,
                                     d_kept_seq, d_kept_w, d_cu_kept, d_n_kept, h_n_kept, d_hidden, d_hidden_k, H,
                                     dtype, d_ids, d_ids_k, d_old_logp, d_old_logp_k, d_ws, ws_bytes,
-                                    (hipStream_t)stream});
+                                    (hipStream_t)stream, false});
 }

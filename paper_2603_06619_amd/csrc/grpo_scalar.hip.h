@@ -14,7 +14,7 @@ struct KlArgs {
   int kind;                // NAT_KL_LOG_RATIO or NAT_KL_NONNEG
 };
 
-struct TokenScalars { float L; float c; float kl; };
+struct TokenScalars { float L; float c; float kl; bool clipped; };   // clipped: A != 0 and dS/dlogp = 0
 
 // r = exp(logp - old_logp); S = min(r A, clip(r, 1-eps_lo, 1+eps_hi) A);
 // dS/dlogp = r A on the unclipped branch (boundaries inclusive), else 0;
@@ -30,6 +30,7 @@ __device__ __forceinline__ TokenScalars grpo_token_scalars(float logp, float old
   const bool active = (A > 0.f && r <= 1.f + eps_hi) || (A < 0.f && r >= 1.f - eps_lo);
   float g = active ? r * A : 0.f;
   TokenScalars out;
+  out.clipped = A != 0.f && !active;
   out.L = S;
   out.kl = 0.f;
   if (beta_kl != 0.f) {

@@ -347,7 +347,8 @@ struct LogitsEpilogue {
     for (int nb = 0; nb < NB; ++nb) {
       const int kk = k0 + nb * 32 + (lane & 31);
       const bool tok_valid = kk < n_valid;
-      pre.y[nb] = tok_valid ? ids[kk] : -1;
+      const int y = tok_valid ? ids[kk] : -1;
+      pre.y[nb] = (y >= 0 && y < V) ? y : -1;              // an id outside the vocabulary matches no row
       pre.shift[nb] = tok_valid ? ref[kk] : 0.f;
     }
   }
@@ -525,14 +526,20 @@ struct DWeightEpilogue {
 
 // ----------------------------------------------------- reference logit ----
 // ref[kk] = h_k . W[ids_k] in fp32, one wavefront per token (row-major caller arrays).
+// An id outside [0, V) reads no row of W and gets the shift 0.
 __global__ void __launch_bounds__(256)
 target_logit_kernel(const uint16_t* __restrict__ hidden, const uint16_t* __restrict__ W, const int32_t* __restrict__ ids,
-                    int n_valid, int H, float* __restrict__ ref) {
+                    int n_valid, int H, int V, float* __restrict__ ref) {
   const int kk = blockIdx.x * 4 + (threadIdx.x >> 6);
   const int lane = threadIdx.x & 63;
   if (kk >= n_valid) return;
+  const int y = ids[kk];
+  if (y < 0 || y >= V) {
+    if (lane == 0) ref[kk] = 0.f;
+    return;
+  }
   const uint4* hp = (const uint4*)(hidden + (int64_t)kk * H);
-  const uint4* wp = (const uint4*)(W + (int64_t)ids[kk] * H);
+  const uint4* wp = (const uint4*)(W + (int64_t)y * H);
   float s = 0.f;
   for (int j = lane; j < H / 8; j += 64) {
     const uint4 a = hp[j], b = wp[j];
@@ -548,80 +555,128 @@ target_logit_kernel(const uint16_t* __restrict__ hidden, const uint16_t* __restr
 }
 
 // ------------------------------------------------- per-token statistics ----
-// 64 tokens per workgroup; the granules of a token are split over 4 wavefronts (granule gi goes
-// to wavefront gi % 4) and the four partial sums are added in wavefront order, so the result
-// does not depend on timing.
-__global__ void __launch_bounds__(256)
-token_stats_kernel(const float* __restrict__ s_part, const float* __restrict__ t_part, int n_granules, int64_t ld,
-                   const float* __restrict__ ref, const float* __restrict__ z_target, int n_valid, int chunk_start,
-                   const float* __restrict__ old_logp, const float* __restrict__ adv,
-                   const int32_t* __restrict__ kept_seq, const float* __restrict__ kept_w,
-                   float eps_lo, float eps_hi, float grad_scale, KlArgs klp,
-                   float* __restrict__ beta_out, float* __restrict__ patch_out,
-                   float* __restrict__ logp_out, float* __restrict__ kl_out, float* __restrict__ entropy_out,
-                   float* __restrict__ term) {
-  __shared__ float s_s[4][64];
-  __shared__ float t_s[4][64];
+// A granule's partial sum at or above e^70 means some numerator reached the range in which the
+// clamp of the exponent shift acts (a clamped numerator alone makes its granule's sum that large).
+constexpr float kShiftRangeLimit = 2.5154386709191669e30f;     // e^70
+
+// Per-token sums of the per-granule partials: 64 tokens per workgroup; the granules of a token are
+// split over 4 wavefronts (granule gi goes to wavefront gi % 4) and the four partial sums are added
+// in wavefront order, so the result does not depend on timing.  Returns to wavefront 0 only.
+struct TokenSums { float S, TZ; bool in_shift_range; };
+
+__device__ __forceinline__ TokenSums token_sums(const float* __restrict__ s_part, const float* __restrict__ t_part,
+                                                int n_granules, int64_t ld, int kk, bool valid,
+                                                float (*s_s)[64], float (*t_s)[64], float (*m_s)[64]) {
   const int t = threadIdx.x & 63, part = threadIdx.x >> 6;
-  const int kk = blockIdx.x * 64 + t;
-  float s = 0.f, tz = 0.f;
-  if (kk < n_valid) {
-    for (int gi = part; gi < n_granules; gi += 4) s += s_part[(int64_t)gi * ld + kk];
+  float s = 0.f, tz = 0.f, mx = 0.f;
+  if (valid) {
+    for (int gi = part; gi < n_granules; gi += 4) {
+      const float v = s_part[(int64_t)gi * ld + kk];
+      s += v;
+      mx = fmaxf(mx, v);
+    }
     if (t_part)
       for (int gi = part; gi < n_granules; gi += 4) tz += t_part[(int64_t)gi * ld + kk];
   }
   s_s[part][t] = s;
   t_s[part][t] = tz;
+  m_s[part][t] = mx;
   __syncthreads();
-  if (part != 0 || kk >= n_valid) return;
-  const float S = (s_s[0][t] + s_s[1][t]) + (s_s[2][t] + s_s[3][t]);
-  const float lse = ref[kk] + logf(S);
-  const float logp = z_target[kk] - lse;
-  const int k = chunk_start + kk;
-  const float w = kept_w[k];
-  const TokenScalars ts = grpo_token_scalars(logp, old_logp[k], adv[kept_seq[k]], w, eps_lo, eps_hi, grad_scale,
-                                             klp.beta, klp.kind, klp.beta != 0.f ? klp.ref_logp[k] : 0.f);
-  beta_out[kk] = -ts.c / S;                            // dz_kv = beta_k E_kv off the target
-  patch_out[kk] = -S * (1.f - __expf(logp));           // E'_target with beta_k E' = c_k (1 - p_target)
-  if (logp_out) logp_out[k] = logp;
-  if (kl_out) kl_out[k] = ts.kl;
-  // -sum_v p_v log p_v with p_v = E_v / S and log p_v = (z_v - ref) - log S
-  if (entropy_out) entropy_out[k] = logf(S) - ((t_s[0][t] + t_s[1][t]) + (t_s[2][t] + t_s[3][t])) / S;
-  term[k] = w * ts.L;
+  TokenSums out;
+  out.S = (s_s[0][t] + s_s[1][t]) + (s_s[2][t] + s_s[3][t]);
+  out.TZ = (t_s[0][t] + t_s[1][t]) + (t_s[2][t] + t_s[3][t]);
+  out.in_shift_range = fmaxf(fmaxf(m_s[0][t], m_s[1][t]), fmaxf(m_s[2][t], m_s[3][t])) >= kShiftRangeLimit;
+  return out;
+}
+
+__global__ void __launch_bounds__(256)
+token_stats_kernel(const float* __restrict__ s_part, const float* __restrict__ t_part, int n_granules, int64_t ld,
+                   const float* __restrict__ ref, const float* __restrict__ z_target, int n_valid, int chunk_start,
+                   const int32_t* __restrict__ ids, int V,
+                   const float* __restrict__ old_logp, const float* __restrict__ adv,
+                   const int32_t* __restrict__ kept_seq, const float* __restrict__ kept_w,
+                   float eps_lo, float eps_hi, float grad_scale, KlArgs klp,
+                   float* __restrict__ beta_out, float* __restrict__ patch_out,
+                   float* __restrict__ logp_out, float* __restrict__ kl_out, float* __restrict__ entropy_out,
+                   float* __restrict__ term, int32_t* __restrict__ diag) {
+  __shared__ float s_s[4][64], t_s[4][64], m_s[4][64];
+  const int t = threadIdx.x & 63, part = threadIdx.x >> 6;
+  const int kk = blockIdx.x * 64 + t;
+  const bool valid = kk < n_valid;
+  const TokenSums sums = token_sums(s_part, t_part, n_granules, ld, kk, valid, s_s, t_s, m_s);
+  if (part != 0) return;                                 // wavefront 0 finishes the 64 tokens
+  bool bad_id = false, clipped = false, nonzero_adv = false;
+  if (valid) {
+    const float S = sums.S;
+    const int k = chunk_start + kk;
+    const int y = ids[kk];
+    bad_id = y < 0 || y >= V;
+    if (entropy_out) entropy_out[k] = logf(S) - sums.TZ / S;   // -sum_v p_v log p_v, p_v = E_v / S
+    if (bad_id) {                                        // left out: no loss term, zero gradient
+      beta_out[kk] = 0.f;
+      patch_out[kk] = 0.f;
+      if (logp_out) logp_out[k] = __builtin_nanf("");
+      if (kl_out) kl_out[k] = __builtin_nanf("");
+      term[k] = 0.f;
+    } else {
+      const float lse = ref[kk] + logf(S);
+      const float logp = z_target[kk] - lse;
+      const float w = kept_w[k];
+      const float A = adv[kept_seq[k]];
+      const TokenScalars ts = grpo_token_scalars(logp, old_logp[k], A, w, eps_lo, eps_hi, grad_scale,
+                                                 klp.beta, klp.kind, klp.beta != 0.f ? klp.ref_logp[k] : 0.f);
+      clipped = ts.clipped;
+      nonzero_adv = A != 0.f;
+      beta_out[kk] = -ts.c / S;                          // dz_kv = beta_k E_kv off the target
+      patch_out[kk] = -S * (1.f - __expf(logp));         // E'_target with beta_k E' = c_k (1 - p_target)
+      if (logp_out) logp_out[k] = logp;
+      if (kl_out) kl_out[k] = ts.kl;
+      term[k] = w * ts.L;
+    }
+  }
+  if (diag) {
+    wave_count(bad_id, diag + NAT_DIAG_BAD_ID);
+    wave_count(valid && sums.in_shift_range, diag + NAT_DIAG_SHIFT_RANGE);
+    wave_count(clipped, diag + NAT_DIAG_CLIPPED);
+    wave_count(nonzero_adv, diag + NAT_DIAG_NONZERO_ADV);
+  }
 }
 
 // Forward pass alone: log-prob of the target (and the entropy) from the per-granule sums.
 __global__ void __launch_bounds__(256)
 logp_stats_kernel(const float* __restrict__ s_part, const float* __restrict__ t_part, int n_granules, int64_t ld,
                   const float* __restrict__ ref, const float* __restrict__ z_target, int n_valid, int chunk_start,
-                  float* __restrict__ logp_out, float* __restrict__ entropy_out) {
-  __shared__ float s_s[4][64];
-  __shared__ float t_s[4][64];
+                  const int32_t* __restrict__ ids, int V,
+                  float* __restrict__ logp_out, float* __restrict__ entropy_out, int32_t* __restrict__ diag) {
+  __shared__ float s_s[4][64], t_s[4][64], m_s[4][64];
   const int t = threadIdx.x & 63, part = threadIdx.x >> 6;
   const int kk = blockIdx.x * 64 + t;
-  float s = 0.f, tz = 0.f;
-  if (kk < n_valid) {
-    for (int gi = part; gi < n_granules; gi += 4) s += s_part[(int64_t)gi * ld + kk];
-    if (t_part)
-      for (int gi = part; gi < n_granules; gi += 4) tz += t_part[(int64_t)gi * ld + kk];
+  const bool valid = kk < n_valid;
+  const TokenSums sums = token_sums(s_part, t_part, n_granules, ld, kk, valid, s_s, t_s, m_s);
+  if (part != 0) return;
+  bool bad_id = false;
+  if (valid) {
+    const int k = chunk_start + kk;
+    const int y = ids[kk];
+    bad_id = y < 0 || y >= V;
+    logp_out[k] = bad_id ? __builtin_nanf("") : z_target[kk] - (ref[kk] + logf(sums.S));
+    if (entropy_out) entropy_out[k] = logf(sums.S) - sums.TZ / sums.S;
   }
-  s_s[part][t] = s;
-  t_s[part][t] = tz;
-  __syncthreads();
-  if (part != 0 || kk >= n_valid) return;
-  const float S = (s_s[0][t] + s_s[1][t]) + (s_s[2][t] + s_s[3][t]);
-  const int k = chunk_start + kk;
-  logp_out[k] = z_target[kk] - (ref[kk] + logf(S));
-  if (entropy_out) entropy_out[k] = logf(S) - ((t_s[0][t] + t_s[1][t]) + (t_s[2][t] + t_s[3][t])) / S;
+  if (diag) {
+    wave_count(bad_id, diag + NAT_DIAG_BAD_ID);
+    wave_count(valid && sums.in_shift_range, diag + NAT_DIAG_SHIFT_RANGE);
+  }
 }
 
-// Overwrite the target entry of every valid token in both copies of E (see token_stats_kernel).
+// Overwrite the target entry of every valid token in both copies of E (see token_stats_kernel);
+// a token whose id lies outside [0, V) has no target entry.
 __global__ void __launch_bounds__(256)
 patch_target_kernel(uint16_t* __restrict__ Et, int kb_e, uint16_t* __restrict__ Eb, int kb_z,
-                    const int32_t* __restrict__ ids, const float* __restrict__ patch, int n_valid) {
+                    const int32_t* __restrict__ ids, const float* __restrict__ patch, int n_valid, int V) {
   const int kk = blockIdx.x * blockDim.x + threadIdx.x;
   if (kk >= n_valid) return;
   const int y = ids[kk];
+  if (y < 0 || y >= V) return;
   const uint16_t bits = f32_to_bf16_bits(patch[kk]);
   Et[blk_off(y, kk, kb_e)] = bits;
   Eb[blk_off(kk, y, kb_z)] = bits;
@@ -740,7 +795,7 @@ nat_status loss_bf16_run(const LossArgs& a) {
       ProfScope prof(PC_TRANSPOSE, s);
       pack_blocked_kernel<<<dim3(np / 64, H / 64), 256, 0, s>>>(hid_c, H, nv, H, np, Hp, Hb, nullptr, nullptr);
       NAT_LAUNCH_CHECK();
-      target_logit_kernel<<<(nv + 3) / 4, 256, 0, s>>>(hid_c, W, a.ids + c0, nv, H, ref);
+      target_logit_kernel<<<(nv + 3) / 4, 256, 0, s>>>(hid_c, W, a.ids + c0, nv, H, V, ref);
       NAT_LAUNCH_CHECK();
     }
     {  // logits: rows = vocabulary, columns = tokens, contraction over the hidden size
@@ -757,12 +812,12 @@ nat_status loss_bf16_run(const LossArgs& a) {
     }
     {
       ProfScope prof(PC_TOKEN_STATS, s);
-      token_stats_kernel<<<(nv + 63) / 64, 256, 0, s>>>(s_part, t_part, p.n_granules, cap, ref, zt, nv, c0, a.old_logp,
-                                                       a.adv, a.kept_seq, a.kept_w, a.eps_lo, a.eps_hi, a.grad_scale,
-                                                       KlArgs{a.ref_logp, a.beta_kl, a.kl_kind}, beta, patch, a.logp,
-                                                       a.kl_out, a.entropy_out, term);
+      token_stats_kernel<<<(nv + 63) / 64, 256, 0, s>>>(s_part, t_part, p.n_granules, cap, ref, zt, nv, c0, a.ids + c0, V,
+                                                       a.old_logp, a.adv, a.kept_seq, a.kept_w, a.eps_lo, a.eps_hi,
+                                                       a.grad_scale, KlArgs{a.ref_logp, a.beta_kl, a.kl_kind}, beta,
+                                                       patch, a.logp, a.kl_out, a.entropy_out, term, a.diag);
       NAT_LAUNCH_CHECK();
-      patch_target_kernel<<<(nv + 255) / 256, 256, 0, s>>>(Et, np / 32, Eb, Vp / 32, a.ids + c0, patch, nv);
+      patch_target_kernel<<<(nv + 255) / 256, 256, 0, s>>>(Et, np / 32, Eb, Vp / 32, a.ids + c0, patch, nv, V);
       NAT_LAUNCH_CHECK();
     }
     {  // (diag(beta) H_chunk)^T in the blocked layout
@@ -819,7 +874,7 @@ nat_status logp_bf16_run(const LogpArgs& a) {
       ProfScope prof(PC_TRANSPOSE, s);
       pack_blocked_kernel<<<dim3(np / 64, H / 64), 256, 0, s>>>(hid_c, H, nv, H, np, H, Hb, nullptr, nullptr);
       NAT_LAUNCH_CHECK();
-      target_logit_kernel<<<(nv + 3) / 4, 256, 0, s>>>(hid_c, W, a.ids + c0, nv, H, ref);
+      target_logit_kernel<<<(nv + 3) / 4, 256, 0, s>>>(hid_c, W, a.ids + c0, nv, H, V, ref);
       NAT_LAUNCH_CHECK();
     }
     {
@@ -836,8 +891,8 @@ nat_status logp_bf16_run(const LogpArgs& a) {
     }
     {
       ProfScope prof(PC_TOKEN_STATS, s);
-      logp_stats_kernel<<<(nv + 63) / 64, 256, 0, s>>>(s_part, t_part, p.n_granules, cap, ref, zt, nv, c0, a.logp,
-                                                      a.entropy);
+      logp_stats_kernel<<<(nv + 63) / 64, 256, 0, s>>>(s_part, t_part, p.n_granules, cap, ref, zt, nv, c0, a.ids + c0, V,
+                                                      a.logp, a.entropy, a.diag);
       NAT_LAUNCH_CHECK();
     }
   }

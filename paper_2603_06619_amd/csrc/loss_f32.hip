@@ -27,7 +27,7 @@ f32_forward_kernel(const float* __restrict__ hidden, const float* __restrict__ W
                    const int32_t* __restrict__ kept_seq, const float* __restrict__ kept_w,
                    int chunk_start, int H, int V, float eps_lo, float eps_hi, float grad_scale, KlArgs klp,
                    float* __restrict__ dz /*[chunk, V]*/, float* __restrict__ logp_out, float* __restrict__ term,
-                   float* __restrict__ kl_out, float* __restrict__ entropy_out) {
+                   float* __restrict__ kl_out, float* __restrict__ entropy_out, int32_t* __restrict__ diag) {
   extern __shared__ float h_s[];             // H floats
   __shared__ float red[4];
   __shared__ float bcast[2];
@@ -66,17 +66,31 @@ f32_forward_kernel(const float* __restrict__ hidden, const float* __restrict__ W
   if (threadIdx.x == 0) {
     const float sum = (red[0] + red[1]) + (red[2] + red[3]);
     const float lse = m + logf(sum);
-    const float logp = z[ids[k]] - lse;
-    const float w = kept_w[k];
-    const TokenScalars ts = grpo_token_scalars(logp, old_logp[k], adv[kept_seq[k]], w, eps_lo, eps_hi, grad_scale,
-                                               klp.beta, klp.kind, klp.beta != 0.f ? klp.ref_logp[k] : 0.f);
-    if (logp_out) logp_out[k] = logp;
-    if (kl_out) kl_out[k] = ts.kl;
     // -sum p log p = log(sum) - (sum of e (z - m)) / sum
     if (entropy_out) entropy_out[k] = logf(sum) - ((red_t[0] + red_t[1]) + (red_t[2] + red_t[3])) / sum;
-    term[k] = w * ts.L;
+    const int yk = ids[k];
     bcast[0] = lse;
-    bcast[1] = ts.c;
+    if (yk < 0 || yk >= V) {                 // no such token: left out (no loss term, zero gradient)
+      if (logp_out) logp_out[k] = __builtin_nanf("");
+      if (kl_out) kl_out[k] = __builtin_nanf("");
+      term[k] = 0.f;
+      bcast[1] = 0.f;
+      if (diag) atomicAdd(diag + NAT_DIAG_BAD_ID, 1);
+    } else {
+      const float logp = z[yk] - lse;
+      const float w = kept_w[k];
+      const float A = adv[kept_seq[k]];
+      const TokenScalars ts = grpo_token_scalars(logp, old_logp[k], A, w, eps_lo, eps_hi, grad_scale,
+                                                 klp.beta, klp.kind, klp.beta != 0.f ? klp.ref_logp[k] : 0.f);
+      if (logp_out) logp_out[k] = logp;
+      if (kl_out) kl_out[k] = ts.kl;
+      term[k] = w * ts.L;
+      bcast[1] = ts.c;
+      if (diag) {
+        if (ts.clipped) atomicAdd(diag + NAT_DIAG_CLIPPED, 1);
+        if (A != 0.f) atomicAdd(diag + NAT_DIAG_NONZERO_ADV, 1);
+      }
+    }
   }
   __syncthreads();
   const float lse = bcast[0], c = bcast[1];
@@ -141,7 +155,7 @@ nat_status loss_f32_run(const LossArgs& a) {
       f32_forward_kernel<<<n, kF32Threads, (size_t)a.H * sizeof(float), s>>>(
           (const float*)a.hidden, (const float*)a.W, a.ids, a.old_logp, a.adv, a.kept_seq, a.kept_w, c0, a.H, a.V,
           a.eps_lo, a.eps_hi, a.grad_scale, KlArgs{a.ref_logp, a.beta_kl, a.kl_kind}, dz, a.logp, term,
-          a.kl_out, a.entropy_out);
+          a.kl_out, a.entropy_out, a.diag);
       NAT_LAUNCH_CHECK();
       f32_dh_kernel<<<n, kF32Threads, 0, s>>>(dz, (const float*)a.W, c0, a.H, a.V, (float*)a.dH);
       NAT_LAUNCH_CHECK();
@@ -163,7 +177,7 @@ nat_status loss_f32_run(const LossArgs& a) {
 __global__ void __launch_bounds__(kF32Threads)
 f32_logp_kernel(const float* __restrict__ hidden, const float* __restrict__ W, const int32_t* __restrict__ ids,
                 int chunk_start, int H, int V, float* __restrict__ z_scratch /*[chunk, V]*/,
-                float* __restrict__ logp_out, float* __restrict__ entropy_out) {
+                float* __restrict__ logp_out, float* __restrict__ entropy_out, int32_t* __restrict__ diag) {
   extern __shared__ float h_s[];
   __shared__ float red[4], red_t[4];
   const int kc = blockIdx.x, k = chunk_start + kc;
@@ -198,7 +212,13 @@ f32_logp_kernel(const float* __restrict__ hidden, const float* __restrict__ W, c
   __syncthreads();
   if (threadIdx.x == 0) {
     const float sum = (red[0] + red[1]) + (red[2] + red[3]);
-    logp_out[k] = z[ids[k]] - (m + logf(sum));
+    const int yk = ids[k];
+    if (yk < 0 || yk >= V) {
+      logp_out[k] = __builtin_nanf("");
+      if (diag) atomicAdd(diag + NAT_DIAG_BAD_ID, 1);
+    } else {
+      logp_out[k] = z[yk] - (m + logf(sum));
+    }
     if (entropy_out) entropy_out[k] = logf(sum) - ((red_t[0] + red_t[1]) + (red_t[2] + red_t[3])) / sum;
   }
 }
@@ -221,7 +241,7 @@ nat_status logp_f32_run(const LogpArgs& a) {
   for (int c0 = 0; c0 < a.N_k; c0 += (int)rows) {
     const int n = a.N_k - c0 < (int)rows ? a.N_k - c0 : (int)rows;
     f32_logp_kernel<<<n, kF32Threads, (size_t)a.H * sizeof(float), s>>>(
-        (const float*)a.hidden, (const float*)a.W, a.ids, c0, a.H, a.V, (float*)a.ws, a.logp, a.entropy);
+        (const float*)a.hidden, (const float*)a.W, a.ids, c0, a.H, a.V, (float*)a.ws, a.logp, a.entropy, a.diag);
     NAT_LAUNCH_CHECK();
   }
   return NAT_OK;

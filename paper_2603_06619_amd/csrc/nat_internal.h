@@ -15,7 +15,7 @@ enum ProfClass : int {
 
 // Brackets the launches issued during its lifetime with two events when timing is on.
 struct ProfScope {
-  ProfScope(int cls, hipStream_t s);
+  ProfScope(int cls, hipStream_t s, bool enabled = true);
   ~ProfScope();
   int cls_; hipStream_t s_; void* rec_;
 };
@@ -53,10 +53,12 @@ nat_status launch_prefix_mask(const int64_t* d_cu, int32_t B, int64_t N, const i
 // the scheme's closed form when d_pi is NULL, else from the given probabilities.
 struct CompactArgs {
   int32_t n_rollouts_global; const uint32_t* mask_bits; const double* pi; const int64_t* cu; int32_t B; int64_t N;
+  int64_t kept_cap;             // capacity of the per-kept-token outputs
   int32_t* kept_idx; int32_t* kept_seq; float* kept_w; int32_t* cu_kept; int32_t* n_kept; int32_t* h_n_kept;
   const void* hidden; void* hidden_k; int32_t H; int32_t dtype;
   const int32_t* ids; int32_t* ids_k; const float* old_logp; float* old_logp_k;
   void* ws; size_t ws_bytes; hipStream_t stream;
+  bool no_timing;               // never create timing events (the entry point that must not allocate)
 };
 nat_status compact_run(const SelectArgs& sel, const CompactArgs& c);
 
@@ -69,6 +71,7 @@ struct LossArgs {
   void* ws; size_t ws_bytes; hipStream_t stream;
   // KL term of Eq. 4 and the diagnostics of nat_loss_fwd_bwd_kl (all optional)
   const float* ref_logp; float beta_kl; int32_t kl_kind; float* kl_out; float* entropy_out;
+  int32_t* diag;                // optional [NAT_DIAG_WORDS] counters, already cleared by the entry point
 };
 size_t loss_bf16_workspace_bytes(int32_t N_k, int32_t H, int32_t V, bool minimal);
 nat_status loss_bf16_run(const LossArgs& a);
@@ -79,6 +82,7 @@ nat_status loss_f32_run(const LossArgs& a);
 struct LogpArgs {
   const void* hidden; const void* W; const int32_t* ids; int32_t N_k, H, V;
   float* logp; float* entropy; void* ws; size_t ws_bytes; hipStream_t stream;
+  int32_t* diag;                // optional [NAT_DIAG_WORDS] counters, already cleared by the entry point
 };
 size_t logp_bf16_workspace_bytes(int32_t N_k, int32_t H, int32_t V, bool minimal);
 nat_status logp_bf16_run(const LogpArgs& a);
@@ -87,5 +91,12 @@ nat_status logp_f32_run(const LogpArgs& a);
 
 // shared small kernels (api.hip)
 nat_status fill_zero_f32(float* p, size_t n, hipStream_t s);
+
+// One atomic per wavefront: adds the number of lanes whose `flag` is set to *counter.  Every lane
+// of the wavefront must call it (integer adds: the total does not depend on their order).
+__device__ __forceinline__ void wave_count(bool flag, int32_t* counter) {
+  const unsigned long long b = __ballot(flag);
+  if (b != 0ull && (threadIdx.x & 63) == 0) atomicAdd(counter, (int32_t)__popcll(b));
+}
 
 }  // namespace nat

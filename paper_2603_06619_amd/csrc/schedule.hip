@@ -38,12 +38,14 @@ __device__ __forceinline__ uint64_t block_scan_u64(uint64_t v, uint64_t* wave_to
 __global__ void __launch_bounds__(kSchedThreads)
 schedule_cut_kernel(uint32_t key0, uint32_t key1, uint32_t step, int32_t rollout_id_base,
                     const float* __restrict__ drop_zero_adv,
-                    const uint32_t* __restrict__ weights, const int64_t* __restrict__ cu,
+                    const uint32_t* __restrict__ weights, const int64_t* __restrict__ cu, int64_t N,
                     int32_t* __restrict__ cut_len, double* __restrict__ pi) {
   __shared__ uint64_t wave_tot[kSchedThreads / 64];
   const int i = blockIdx.x;
-  const int64_t start = cu[i];
-  const int64_t T = cu[i + 1] - start;
+  // offsets are clamped to the N positions the caller's arrays hold
+  const int64_t start = cu[i] < 0 ? 0 : cu[i] > N ? N : cu[i];
+  const int64_t stop = cu[i + 1] > N ? N : cu[i + 1];
+  const int64_t T = stop - start;
   if (T <= 0) {
     if (threadIdx.x == 0) cut_len[i] = 0;
     return;
@@ -104,7 +106,8 @@ poisson_mask_kernel(uint32_t key0, uint32_t key1, uint32_t step, int32_t rollout
                     const int64_t* __restrict__ cu, int B, int64_t N, uint32_t* __restrict__ mask_bits) {
   const int64_t n0 = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4;
   uint32_t nibble = 0;
-  if (n0 < N) {
+  const int64_t n_end = cu[B] < N ? cu[B] : N;     // positions beyond the last rollout are never kept
+  if (n0 < n_end) {
     int i = rollout_of_pos(cu, 0, B, n0);
     int64_t start = cu[i], end = cu[i + 1];
     bool dropped = drop_zero_adv && drop_zero_adv[i] == 0.f;
@@ -113,9 +116,9 @@ poisson_mask_kernel(uint32_t key0, uint32_t key1, uint32_t step, int32_t rollout
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       const int64_t n = n0 + j;
-      if (n >= N) break;
+      if (n >= n_end) break;
       if (n >= end) {
-        do { ++i; } while (cu[i + 1] <= n);
+        do { ++i; } while (i < B - 1 && cu[i + 1] <= n);
         start = cu[i];
         end = cu[i + 1];
         dropped = drop_zero_adv && drop_zero_adv[i] == 0.f;
@@ -242,7 +245,7 @@ extern "C" nat_status nat_select_schedule(const nat_select_params* params, const
   ProfScope prof(PC_SCHEDULE, s);
   schedule_cut_kernel<<<(unsigned)B, kSchedThreads, 0, s>>>(
       (uint32_t)(params->seed & 0xFFFFFFFFull), (uint32_t)(params->seed >> 32), params->step,
-      params->rollout_id_base, params->d_drop_zero_adv, d_weights, d_cu_seqlens, d_cut_len, d_pi);
+      params->rollout_id_base, params->d_drop_zero_adv, d_weights, d_cu_seqlens, N, d_cut_len, d_pi);
   NAT_LAUNCH_CHECK();
   return launch_prefix_mask(d_cu_seqlens, B, N, d_cut_len, d_mask_bits, s);
 }

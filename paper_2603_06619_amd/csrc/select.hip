@@ -59,7 +59,9 @@ select_mask_kernel(SelectArgs a, const int64_t* __restrict__ cu, int B, int64_t 
                    const int32_t* __restrict__ cut_len, uint32_t* __restrict__ mask_bits) {
   const int64_t n0 = ((int64_t)blockIdx.x * 256 + threadIdx.x) * kSelPerLane;
   uint32_t nibble = 0;
-  if (n0 < N) {
+  // positions at or beyond cu[B] belong to no rollout (the host-passed N may be larger): never kept
+  const int64_t n_end = cu[B] < N ? cu[B] : N;
+  if (n0 < n_end) {
     int i = rollout_of_pos(cu, 0, B, n0);
     int64_t start = cu[i], end = cu[i + 1];
     int scheme = a.scheme_per_rollout ? a.scheme_per_rollout[i] : a.scheme;
@@ -70,9 +72,9 @@ select_mask_kernel(SelectArgs a, const int64_t* __restrict__ cu, int B, int64_t 
 #pragma unroll
     for (int j = 0; j < kSelPerLane; ++j) {
       const int64_t n = n0 + j;
-      if (n >= N) break;
-      if (n >= end) {                              // next non-empty rollout
-        do { ++i; } while (cu[i + 1] <= n);
+      if (n >= n_end) break;
+      if (n >= end) {                              // next non-empty rollout (n < cu[B]: one exists below B)
+        do { ++i; } while (i < B - 1 && cu[i + 1] <= n);
         start = cu[i];
         end = cu[i + 1];
         scheme = a.scheme_per_rollout ? a.scheme_per_rollout[i] : a.scheme;

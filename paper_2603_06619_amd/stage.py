@@ -85,7 +85,7 @@ class LossStage:
         out["total"], out["max_len"] = int(self.h_totals[0]), int(self.h_totals[1])
         return out
 
-    def logp(self, hidden_k, W, ids_k, N_k, want_entropy=False, ws_bytes=None):
+    def logp(self, hidden_k, W, ids_k, N_k, want_entropy=False, ws_bytes=None, want_diag=False):
         """Forward pass alone: log-probs (and entropies) of the given tokens."""
         dev = self.device
         V, H = W.shape
@@ -94,13 +94,15 @@ class LossStage:
             ws_bytes = nb.logp_workspace_bytes(N_k, H, V, dt)
         ws = self._buf("loss", max(ws_bytes, 256))[:max(ws_bytes, 256)]
         out = dict(logp=torch.empty(max(N_k, 1), dtype=torch.float32, device=dev),
-                   entropy=torch.empty(max(N_k, 1), dtype=torch.float32, device=dev) if want_entropy else None)
-        nb.nat_logp_fwd(hidden_k, W, ids_k, N_k, out["logp"], out["entropy"], ws)
+                   entropy=torch.empty(max(N_k, 1), dtype=torch.float32, device=dev) if want_entropy else None,
+                   diag=torch.empty(nb.DIAG_WORDS, dtype=torch.int32, device=dev) if want_diag else None)
+        nb.nat_logp_fwd(hidden_k, W, ids_k, N_k, out["logp"], out["entropy"], ws, out["diag"])
         return out
 
     def loss(self, hidden_k, W, ids_k, old_logp_k, adv, kept_seq, kept_w, N_k, eps_lo=0.2, eps_hi=0.2,
              grad_scale=1.0, dW=None, accumulate_dw=False, ws_bytes=None, want_logp=True,
-             ref_logp_k=None, beta_kl=0.0, kl_kind=nb.KL_LOG_RATIO, want_kl=False, want_entropy=False):
+             ref_logp_k=None, beta_kl=0.0, kl_kind=nb.KL_LOG_RATIO, want_kl=False, want_entropy=False,
+             want_diag=False):
         dev = self.device
         V, H = W.shape
         dt = nb.DTYPE_BF16 if W.dtype == torch.bfloat16 else nb.DTYPE_F32
@@ -111,14 +113,15 @@ class LossStage:
                    logp=torch.empty(max(N_k, 1), dtype=torch.float32, device=dev) if want_logp else None,
                    dH=torch.empty((max(N_k, 1), H), dtype=W.dtype, device=dev),
                    dW=dW if dW is not None else torch.empty((V, H), dtype=torch.float32, device=dev))
-        if ref_logp_k is None and not want_kl and not want_entropy:
+        if ref_logp_k is None and not want_kl and not want_entropy and not want_diag:
             nb.nat_loss_fwd_bwd(hidden_k, W, ids_k, old_logp_k, adv, kept_seq, kept_w, N_k, eps_lo, eps_hi, grad_scale,
                                 out["loss"], out["logp"], out["dH"], out["dW"], accumulate_dw, ws)
             return out
         f32 = lambda: torch.empty(max(N_k, 1), dtype=torch.float32, device=dev)
         out["kl"] = f32() if want_kl else None
         out["entropy"] = f32() if want_entropy else None
+        out["diag"] = torch.empty(nb.DIAG_WORDS, dtype=torch.int32, device=dev) if want_diag else None
         nb.nat_loss_fwd_bwd_kl(hidden_k, W, ids_k, old_logp_k, adv, kept_seq, kept_w, N_k, eps_lo, eps_hi, grad_scale,
                                ref_logp_k, beta_kl, kl_kind, out["loss"], out["logp"], out["kl"], out["entropy"],
-                               out["dH"], out["dW"], accumulate_dw, ws)
+                               out["dH"], out["dW"], accumulate_dw, ws, out["diag"])
         return out

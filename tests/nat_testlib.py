@@ -18,6 +18,50 @@ def max_rel_err(got, ref):
     return float(np.abs(got - ref).max() / den) if den > 0 else float(np.abs(got).max())
 
 
+def rel_frobenius(got, ref):
+    got = np.asarray(got, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    den = np.linalg.norm(ref)
+    return float(np.linalg.norm(got - ref) / den) if den > 0 else float(np.linalg.norm(got))
+
+
+def contraction_errors(dH_got, dW_got, ref, hidden, W, ids, out_ulp):
+    """Errors of the parts of dH and dW that only the two backward contractions produce.
+
+    dz_k = c_k (onehot(y_k) - softmax_k) splits each gradient into the one-hot term (c_k W[y_k] in
+    dH_k, c_k h_k added to row y_k of dW) and the soft-max term (-c_k sum_v p_kv W_v, resp.
+    -sum_k c_k p_kv h_k).  With a near-uniform soft-max the one-hot term dominates the tensors'
+    maxima, so a max-norm over the whole tensor says little about the contractions.  Here:
+      dW_off  rows of dW no token targets (soft-max term alone): ||got - ref||_inf over those rows,
+              divided by the largest off-target entry of the oracle;
+      dH_res  dH with the one-hot term c_k W[y_k] (oracle's c_k, fp64) taken off both sides,
+              divided by the largest entry of the oracle's residual.  dH is stored in the input
+              element type, so each entry also carries the rounding of the FULL value:
+              out_ulp * |dH_ref| (the caller's figure for that rounding) is allowed on top, entry by entry;
+              the returned figure is max over entries of (|diff| - out_ulp |dH_ref|)+ / max|residual|.
+    Also relative Frobenius errors of the whole tensors (reported, not asserted)."""
+    ids = np.asarray(ids, dtype=np.int64)
+    W64 = np.asarray(W, dtype=np.float64)
+    dH_got = np.asarray(dH_got, dtype=np.float64)
+    dW_got = np.asarray(dW_got, dtype=np.float64)
+    onehot_dH = ref["c"][:, None] * W64[ids]
+    res_ref = ref["dH"] - onehot_dH
+    diff = np.abs(dH_got - ref["dH"]) - out_ulp * np.abs(ref["dH"])
+    den = np.abs(res_ref).max()
+    dH_res = float(np.maximum(diff, 0.0).max() / den) if den > 0 else float(np.maximum(diff, 0.0).max())
+    off = np.ones(W64.shape[0], dtype=bool)
+    off[ids] = False
+    if off.any():
+        den_off = np.abs(ref["dW"][off]).max()
+        dW_off = float(np.abs(dW_got[off] - ref["dW"][off]).max() / den_off) if den_off > 0 else 0.0
+        off_share = float(den_off / np.abs(ref["dW"]).max())
+    else:
+        dW_off, off_share = 0.0, 1.0
+    return dict(dH_res=dH_res, dW_off=dW_off, dW_off_share=off_share,
+                dH_res_share=float(den / np.abs(ref["dH"]).max()) if np.abs(ref["dH"]).max() > 0 else 0.0,
+                dH_fro=rel_frobenius(dH_got, ref["dH"]), dW_fro=rel_frobenius(dW_got, ref["dW"]))
+
+
 def to_dev(x, dtype=None):
     t = torch.from_numpy(np.ascontiguousarray(x))
     if dtype is not None:

@@ -59,7 +59,7 @@ def check_diag(out, ref, n, tol):
 def test_fp32_path_with_kl_and_entropy(stage, kind, n_tok, H, V):
     case = add_ref(make_loss_case(40 + n_tok, n_tok, H, V, "f32", noise=0.15), 1)
     out, ref = run_both(stage, case, "f32", 0.3, kind)
-    check(out, ref, n_tok, TOL_F32)
+    check(out, ref, n_tok, TOL_F32, case)
     check_diag(out, ref, n_tok, 1e-5)
 
 
@@ -68,7 +68,7 @@ def test_fp32_path_with_kl_and_entropy(stage, kind, n_tok, H, V):
 def test_bf16_path_with_kl_and_entropy(stage, kind, n_tok, H, V):
     case = add_ref(make_loss_case(140 + n_tok, n_tok, H, V, "bf16", noise=0.15, w_std=0.1), 2)
     out, ref = run_both(stage, case, "bf16", 0.25, kind, grad_scale=2.0)
-    check(out, ref, n_tok, TOL_BF16)
+    check(out, ref, n_tok, TOL_BF16, case)
     check_diag(out, ref, n_tok, 1e-4)
     # the KL term is not a rounding-level effect here: without it the gradient differs visibly
     base = oracle_loss(**{k: v for k, v in case.items() if k != "ref_logp"}, grad_scale=2.0)
@@ -86,7 +86,7 @@ def test_bf16_entropy_of_peaked_and_flat_policies(stage):
     logp = ogrpo.token_logp(case["hidden"], case["W"], case["ids"])
     case["old_logp"] = (logp + np.random.default_rng(5).standard_normal(n_tok) * 0.1).astype(np.float32)
     out, ref = run_both(stage, add_ref(case, 3), "bf16", 0.1, ogrpo.KL_NONNEG)
-    check(out, ref, n_tok, TOL_BF16)
+    check(out, ref, n_tok, TOL_BF16, case)
     check_diag(out, ref, n_tok, 1e-4)
     assert ref["entropy"].min() < 0.5 and ref["entropy"].max() > 2.0
     # flat policy: a zero head gives the uniform distribution, entropy ln V
@@ -116,13 +116,13 @@ def test_bf16_multiple_chunks_with_kl(stage, kind):
     out_c = hip_loss(stage, {k: v for k, v in case.items() if k != "ref_logp"}, "bf16",
                      ref_logp_k=to_dev(case["ref_logp"]), beta_kl=0.5, kl_kind=kind, want_kl=True, want_entropy=True,
                      ws_bytes=ws_min)
-    check(out_c, ref, n_tok, TOL_BF16)
+    check(out_c, ref, n_tok, TOL_BF16, case)
     check_diag(out_c, ref, n_tok, 1e-4)
 
 
 def test_bf16_qwen3_8b_head_reduced_batch_with_kl_and_entropy(stage):
     case = add_ref(make_loss_case(22, 130, 4096, 151936, "bf16"), 5, spread=0.1)
     out, ref = run_both(stage, case, "bf16", 0.04, ogrpo.KL_NONNEG)
-    errs = check(out, ref, 130, TOL_BF16)
+    errs = check(out, ref, 130, TOL_BF16, case, label="qwen3-8B head with KL")
     diag = check_diag(out, ref, 130, 1e-4)
     print("qwen3-8B head reduced batch with KL: rel err logp/dH/dW =", errs, " kl/entropy =", diag)

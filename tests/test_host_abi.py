@@ -76,7 +76,7 @@ def test_compact_argument_errors(lib):
     fake = ctypes.c_void_p(256)
     ok = ctypes.byref(_params(nat))
     args = lambda **kw: [kw.get("params", ok), kw.get("nroll", 4), fake, fake, kw.get("B", 4), kw.get("N", 100),
-                         fake, fake, fake, fake, fake, None,
+                         kw.get("cap", 100), kw.get("idx", fake), fake, fake, fake, fake, None,
                          kw.get("hidden", None), kw.get("hidden_k", None), kw.get("H", 0), kw.get("dtype", 0),
                          None, None, None, None, kw.get("ws", fake), kw.get("ws_bytes", 1 << 20), None]
     assert lib.nat_compact(*args(nroll=0)) == 1
@@ -87,6 +87,8 @@ def test_compact_argument_errors(lib):
     assert lib.nat_compact(*args(hidden=ctypes.c_void_p(260), hidden_k=fake, H=64, dtype=1)) == 1   # misaligned rows
     assert lib.nat_compact(*args(ws_bytes=8)) == 3
     assert lib.nat_compact(*args(ws=None)) == 3
+    assert lib.nat_compact(*args(cap=-1)) == 1                            # negative capacity of the kept-token outputs
+    assert lib.nat_compact(*args(idx=None)) == 1                          # outputs required when the capacity is positive
 
 
 def test_schedule_poisson_and_pack_argument_errors(lib):
@@ -103,12 +105,13 @@ def test_schedule_poisson_and_pack_argument_errors(lib):
     assert lib.nat_select_poisson(ok, None, fake, 4, 10, fake, None) == 1
     assert lib.nat_select_poisson(ok, fake, fake, 4, -1, fake, None) == 1
     assert lib.nat_select_poisson(ok, fake, fake, 4, 10, None, None) == 1
-    cargs = lambda **kw: [kw.get("nroll", 4), fake, kw.get("pi", fake), fake, kw.get("B", 4), 100,
+    cargs = lambda **kw: [kw.get("nroll", 4), fake, kw.get("pi", fake), fake, kw.get("B", 4), 100, kw.get("cap", 100),
                           fake, fake, fake, fake, fake, None, None, None, 0, 0, None, None, None, None,
                           fake, kw.get("ws_bytes", 1 << 20), None]
     assert lib.nat_compact_pi(*cargs(pi=None)) == 1
     assert lib.nat_compact_pi(*cargs(nroll=0)) == 1
     assert lib.nat_compact_pi(*cargs(ws_bytes=8)) == 3
+    assert lib.nat_compact_pi(*cargs(cap=-5)) == 1
     pargs = lambda **kw: [kw.get("P", fake), kw.get("cu", fake), fake, kw.get("B", 4), kw.get("shift", 1),
                           kw.get("rows", 100), kw.get("kept", 50), fake, fake, kw.get("src", fake), fake, fake,
                           kw.get("tot", fake), None, kw.get("ids", None), None, None]
@@ -147,7 +150,7 @@ def test_loss_kl_argument_errors(lib):
     f = ctypes.c_float
     def call(beta=0.1, kind=0, ref=fake, dtype=1, ws_bytes=1 << 34, N_k=10):
         return lib.nat_loss_fwd_bwd_kl(fake, fake, fake, fake, fake, fake, fake, N_k, 64, 512, dtype, f(0.2), f(0.2),
-                                       f(1.0), ref, f(beta), kind, fake, None, None, None, fake, fake, 0, fake,
+                                       f(1.0), ref, f(beta), kind, fake, None, None, None, None, fake, fake, 0, fake,
                                        ws_bytes, None)
     assert call(beta=-0.5) == 1
     assert call(beta=float("nan")) == 1
@@ -160,7 +163,7 @@ def test_loss_kl_argument_errors(lib):
 def test_logp_fwd_argument_errors(lib):
     fake = ctypes.c_void_p(256)
     def call(N_k=10, H=64, V=512, dtype=1, hidden=fake, W=fake, logp=fake, ws=fake, ws_bytes=1 << 34):
-        return lib.nat_logp_fwd(hidden, W, fake, N_k, H, V, dtype, logp, None, ws, ws_bytes, None)
+        return lib.nat_logp_fwd(hidden, W, fake, N_k, H, V, dtype, logp, None, None, ws, ws_bytes, None)
     assert call(dtype=3) == 4
     assert call(N_k=-1) == 1
     assert call(H=100) == 2 and call(V=0) == 2

@@ -162,6 +162,30 @@ nat_status nat_compact(const nat_select_params* params, int32_t n_rollouts_globa
                        void* d_ws, size_t ws_bytes, void* stream);
 
 /*
+ * nat_compact for callers that cannot allocate device memory or hand over a workspace: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid allocation.  Same
+ * arguments (minus the workspace), same kernels and bit-identical outputs; the tile counts and
+ * offsets live in a scratch array that is part of the library's device image (about 513 KiB,
+ * resident on each GPU the library is used on until the process ends).  The call itself
+ * allocates and frees nothing, on the device or through any runtime routine, and never creates
+ * timing events (nat_profile_enable does not see it).
+ *   N may not exceed NAT_COMPACT_STATIC_MAX_TOKENS -> NAT_BAD_SHAPE.
+ *   The device is the one current on the calling thread; `stream` must belong to it.
+ *   All calls on one GPU share that GPU's scratch: calls that overlap in time on one GPU
+ *   (different streams, different threads) race and give undefined results; calls ordered by
+ *   a stream or by events are fine, and nothing needs clearing in between.
+ * Other errors: as nat_compact; a failing symbol lookup -> NAT_HIP_ERROR.
+ */
+#define NAT_COMPACT_STATIC_MAX_TOKENS 268435456   /* 2^28 */
+nat_status nat_compact_static(const nat_select_params* params, int32_t n_rollouts_global,
+                              const uint32_t* d_mask_bits, const int64_t* d_cu_seqlens, int32_t B, int64_t N,
+                              int64_t kept_cap, int32_t* d_kept_idx, int32_t* d_kept_seq, float* d_kept_w,
+                              int32_t* d_cu_kept, int32_t* d_n_kept, int32_t* h_n_kept,
+                              const void* d_hidden, void* d_hidden_k, int32_t H, int32_t dtype,
+                              const int32_t* d_ids, int32_t* d_ids_k,
+                              const float* d_old_logp, float* d_old_logp_k, void* stream);
+
+/*
  * Cut every rollout by its own cut-length distribution (Sec. 4, Eq. 7-8: L_i ~ q_i,
  * mask 1{t <= L_i}, survival p_{i,t} = sum_{l >= t} q_i(l)).
  *   d_weights [N] uint32: non-negative integer weights a_{i,l}, one per response

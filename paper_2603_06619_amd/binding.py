@@ -77,6 +77,9 @@ def load_library():
     lib.nat_compact.restype = i32
     lib.nat_compact.argtypes = [pp, i32, vp, vp, i32, i64, i64, vp, vp, vp, vp, vp, vp, vp, vp, i32, i32,
                                 vp, vp, vp, vp, vp, sz, vp]
+    lib.nat_compact_static.restype = i32
+    lib.nat_compact_static.argtypes = [pp, i32, vp, vp, i32, i64, i64, vp, vp, vp, vp, vp, vp, vp, vp, i32, i32,
+                                       vp, vp, vp, vp, vp]
     lib.nat_select_schedule.restype = i32
     lib.nat_select_schedule.argtypes = [pp, vp, vp, i32, i64, vp, vp, vp, vp]
     lib.nat_select_poisson.restype = i32
@@ -196,6 +199,20 @@ def nat_compact(params, n_rollouts_global, mask_bits, cu_seqlens, B, N, kept_idx
         _ptr(kept_w), _ptr(cu_kept), _ptr(n_kept), _ptr(h_n_kept), _ptr(hidden), _ptr(hidden_k), H, dt,
         _ptr(ids), _ptr(ids_k), _ptr(old_logp), _ptr(old_logp_k), _ptr(workspace),
         workspace.numel() * workspace.element_size() if workspace is not None else 0, _stream()), "nat_compact")
+
+
+def nat_compact_static(params, n_rollouts_global, mask_bits, cu_seqlens, B, N, kept_idx, kept_seq, kept_w, cu_kept,
+                       n_kept, h_n_kept, hidden=None, hidden_k=None, ids=None, ids_k=None,
+                       old_logp=None, old_logp_k=None, kept_cap=None):
+    """nat_compact without a workspace argument (the library's resident scratch); allocates nothing."""
+    c = params._c()
+    H = hidden.shape[1] if hidden is not None else 0
+    dt = _dtype_code(hidden) if hidden is not None else DTYPE_F32
+    _raise(load_library().nat_compact_static(
+        ctypes.byref(c), n_rollouts_global, _ptr(mask_bits), _ptr(cu_seqlens), B, N, _kept_cap(kept_cap, kept_idx),
+        _ptr(kept_idx), _ptr(kept_seq), _ptr(kept_w), _ptr(cu_kept), _ptr(n_kept), _ptr(h_n_kept), _ptr(hidden),
+        _ptr(hidden_k), H, dt, _ptr(ids), _ptr(ids_k), _ptr(old_logp), _ptr(old_logp_k), _stream()),
+        "nat_compact_static")
 
 
 def nat_select_schedule(params, weights, cu_seqlens, B, N, cut_len_out, mask_bits_out, pi_out):

@@ -9,6 +9,8 @@
 // with a ballot prefix so that consecutive lanes write consecutive outputs.
 #include "nat_internal.h"
 
+#include <mutex>
+
 namespace nat {
 
 constexpr int kTileTokens = 4096;                 // tokens per scatter block
@@ -167,7 +169,37 @@ gather_rows_kernel(const int32_t* __restrict__ kept_idx, const int32_t* __restri
   }
 }
 
-static inline int64_t n_tiles_of(int64_t N) { return (N + kTileTokens - 1) / kTileTokens; }
+constexpr int64_t n_tiles_of(int64_t N) { return (N + kTileTokens - 1) / kTileTokens; }
+
+// tile_count[n_tiles] + tile_offset[n_tiles + 1], int32, rounded up to 256 bytes
+constexpr size_t compact_ws_bytes(int64_t N) {
+  return (((size_t)(2 * n_tiles_of(N) + 1) * sizeof(int32_t) + 255) / 256) * 256 + 256;
+}
+
+// Scratch of nat_compact_static: the tile counts and offsets of up to NAT_COMPACT_STATIC_MAX_TOKENS
+// tokens (about 513 KiB), resident on every GPU the library runs on until the process ends.  In host
+// code this name stands for the symbol, not for a device address: the address on each device comes
+// from hipGetSymbolAddress (static_scratch below) and only that pointer is handed to kernels.
+constexpr size_t kStaticScratchBytes = compact_ws_bytes(NAT_COMPACT_STATIC_MAX_TOKENS);
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+static std::mutex g_scratch_mutex;
+static void* g_scratch_ptr[kMaxDevices];          // per device: each GPU has its own copy at its own address
+
+// Address of `scratch` on the current device, looked up once per device.
+static nat_status static_scratch(void** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return NAT_HIP_ERROR;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return NAT_HIP_ERROR;
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return NAT_OK;
+}
 
 }  // namespace nat
 
@@ -175,9 +207,7 @@ using namespace nat;
 
 extern "C" size_t nat_compact_workspace_bytes(int64_t N) {
   if (N < 0) return 0;
-  // tile_count[n_tiles] + tile_offset[n_tiles + 1], int32, rounded up to 256 bytes
-  const size_t ints = (size_t)(2 * n_tiles_of(N) + 1);
-  return ((ints * sizeof(int32_t) + 255) / 256) * 256 + 256;
+  return compact_ws_bytes(N);
 }
 
 namespace nat {
@@ -272,4 +302,26 @@ extern "C" nat_status nat_compact_pi(int32_t n_rollouts_global, const uint32_t* 
                                     d_kept_seq, d_kept_w, d_cu_kept, d_n_kept, h_n_kept, d_hidden, d_hidden_k, H,
                                     dtype, d_ids, d_ids_k, d_old_logp, d_old_logp_k, d_ws, ws_bytes,
                                     (hipStream_t)stream, false});
+}
+
+extern "C" nat_status nat_compact_static(const nat_select_params* params, int32_t n_rollouts_global,
+                                         const uint32_t* d_mask_bits, const int64_t* d_cu_seqlens, int32_t B,
+                                         int64_t N, int64_t kept_cap, int32_t* d_kept_idx, int32_t* d_kept_seq,
+                                         float* d_kept_w, int32_t* d_cu_kept, int32_t* d_n_kept, int32_t* h_n_kept,
+                                         const void* d_hidden, void* d_hidden_k, int32_t H, int32_t dtype,
+                                         const int32_t* d_ids, int32_t* d_ids_k,
+                                         const float* d_old_logp, float* d_old_logp_k, void* stream) {
+  SelectArgs a;
+  nat_status st = validate_select(params, &a);
+  if (st != NAT_OK) return st;
+  if (N > NAT_COMPACT_STATIC_MAX_TOKENS) return NAT_BAD_SHAPE;      // beyond the resident scratch
+  void* ws = nullptr;
+  st = static_scratch(&ws);
+  if (st != NAT_OK) return st;
+  // every word of the scratch that the kernels read is written earlier in the same call (the tile
+  // counts by the count pass, the offsets by the scan), so nothing has to be cleared between calls
+  return compact_run(a, CompactArgs{n_rollouts_global, d_mask_bits, nullptr, d_cu_seqlens, B, N, kept_cap, d_kept_idx,
+                                    d_kept_seq, d_kept_w, d_cu_kept, d_n_kept, h_n_kept, d_hidden, d_hidden_k, H,
+                                    dtype, d_ids, d_ids_k, d_old_logp, d_old_logp_k, ws, kStaticScratchBytes,
+                                    (hipStream_t)stream, true});
 }

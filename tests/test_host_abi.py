@@ -87,6 +87,9 @@ def test_compact_argument_errors(lib):
     assert lib.nat_compact(*args(hidden=ctypes.c_void_p(260), hidden_k=fake, H=64, dtype=1)) == 1   # misaligned rows
     assert lib.nat_compact(*args(ws_bytes=8)) == 3
     assert lib.nat_compact(*args(ws=None)) == 3
+    sargs = lambda **kw: args(**kw)[:-3] + [None]                         # the variant without a workspace
+    assert lib.nat_compact_static(*sargs(N=(1 << 28) + 1)) == 2           # beyond its resident scratch
+    assert lib.nat_compact_static(*sargs(params=None)) == 1
     assert lib.nat_compact(*args(cap=-1)) == 1                            # negative capacity of the kept-token outputs
     assert lib.nat_compact(*args(idx=None)) == 1                          # outputs required when the capacity is positive
 

@@ -21,9 +21,12 @@ def hipcc():
     return os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
 
-def build(verbose=False, extra_flags=()):
-    """Compile every source to an object file (in parallel) and link the shared library."""
-    obj_dir = os.path.join(PKG_DIR, "_build")
+def build(verbose=False, extra_flags=(), lib_path=None, obj_dir=None, link_flags=()):
+    """Compile every source to an object file (in parallel) and link the shared library.
+    lib_path / obj_dir: build somewhere else than in the package (a variant build, e.g. with
+    host-side sanitizers); extra_flags go to every compile line, link_flags to the link line."""
+    obj_dir = obj_dir or os.path.join(PKG_DIR, "_build")
+    lib_path = lib_path or LIB_PATH
     os.makedirs(obj_dir, exist_ok=True)
     procs = []
     for src in SOURCES:
@@ -41,11 +44,11 @@ def build(verbose=False, extra_flags=()):
         if verbose and out.strip():
             print(out)
         objs.append(obj)
-    cmd = [hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", LIB_PATH]
+    cmd = [hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", *link_flags, *objs, "-o", lib_path]
     res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
     if res.returncode != 0:
         raise RuntimeError(f"link failed:\n{res.stdout}")
-    return LIB_PATH
+    return lib_path
 
 
 if __name__ == "__main__":

@@ -68,6 +68,10 @@ constexpr int kTileBytes = kBM * kBK * 2;         // 16 KiB per operand per stag
 #define NAT_WAVES_DWEIGHT 8
 #endif
 constexpr int kMaxChunk = 32768;                  // token rows per chunk (recommended workspace)
+#ifndef NAT_SUBCHUNK
+#define NAT_SUBCHUNK 8192
+#endif
+constexpr int kSubChunk = NAT_SUBCHUNK;           // token rows per launch of the logits and dH contractions
 
 // two floats -> two bf16 in one 32-bit word (lo in bits 0..15): one packed conversion instruction
 __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
@@ -99,9 +103,12 @@ __host__ __device__ __forceinline__ int64_t blk_off(int row, int k, int kb) {
 //   out_rk: rows = r (padded to Rp, multiple of 256), k = c (C must be a multiple of 32);
 //   out_cr: rows = c (padded to Cp, multiple of 256), k = r (padded to Rp).
 //   row_scale: optional [R] factor applied to row r of the input in out_cr (fp32 product, rounded once).
+//   kb_cr: k-slices of the operand out_cr belongs to (Rp / 32 when the input is the whole operand;
+//          more when the rows are a range of a longer contraction axis: out_cr then points at the
+//          range's first k-slice).
 __global__ void __launch_bounds__(256)
 pack_blocked_kernel(const uint16_t* __restrict__ in, int64_t ld_in, int R, int C, int Rp, int Cp,
-                    uint16_t* __restrict__ out_rk, uint16_t* __restrict__ out_cr,
+                    uint16_t* __restrict__ out_rk, uint16_t* __restrict__ out_cr, int kb_cr,
                     const float* __restrict__ row_scale) {
   __shared__ uint16_t tile[64][66];
   const int r0 = blockIdx.x * 64, c0 = blockIdx.y * 64;
@@ -119,7 +126,7 @@ pack_blocked_kernel(const uint16_t* __restrict__ in, int64_t ld_in, int R, int C
   __syncthreads();
   for (int j = ty; j < 64; j += 4) {
     const int c = c0 + j, r = r0 + tx;
-    out_cr[blk_off(c, r, Rp >> 5)] = tile[tx][j];
+    out_cr[blk_off(c, r, kb_cr)] = tile[tx][j];
   }
 }
 
@@ -360,13 +367,13 @@ struct LogitsEpilogue {
     const int l32 = lane & 31, lhi = lane >> 5;
     const int granule = v0 / kGranule;
     const bool all_rows_valid = v0 + kGranule <= V;
+    const bool odd = lane & 1;
+    constexpr float kLog2e = 1.44269504088896340736f, kLn2 = 0.69314718055994530942f;
+
+    // exact target logit, if the target row lies in this granule and in this lane's half
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) {
-      const int kk = k0 + nb * 32 + l32;                 // token column (always inside the padded chunk)
-      const int y = pre.y[nb];
-      const float shift = pre.shift[nb];
-      // exact target logit, if the target row lies in this granule and in this lane's half
-      const int yrel = y - v0;
+      const int yrel = pre.y[nb] - v0;
       if (__any(yrel >= 0 && yrel < kGranule)) {
         if (yrel >= 0 && yrel < kGranule && ((yrel >> 2) & 1) == lhi) {
           float zt = 0.f;
@@ -375,93 +382,93 @@ struct LogitsEpilogue {
 #pragma unroll
             for (int r = 0; r < 16; ++r)
               if (yrel == mb * 32 + 8 * (r >> 2) + 4 * lhi + (r & 3)) zt = acc[mb][nb][r];
-          z_target[kk] = zt;
+          z_target[k0 + nb * 32 + l32] = zt;
         }
-      }
-      // E = exp(min(z - shift, 70)) as 2^(min(z * log2(e) - shift * log2(e), 70 * log2(e))): one fma, one
-      // min and the hardware exponential per logit.  Sixteen logits at a time with independent
-      // temporaries and four running sums, so that the dependent-instruction latency of a lone
-      // wavefront per SIMD is overlapped; only the last vocabulary tile pays for the row check.
-      constexpr float kLog2e = 1.44269504088896340736f, kLn2 = 0.69314718055994530942f;
-      const float nshift2 = -shift * kLog2e;
-      float s4[4] = {0.f, 0.f, 0.f, 0.f}, t4[4] = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-      for (int mb = 0; mb < 4; ++mb) {
-        float x2[16], e[16];
-#pragma unroll
-        for (int r = 0; r < 16; ++r) x2[r] = fminf(fmaf(acc[mb][nb][r], kLog2e, nshift2), 70.f * kLog2e);
-#pragma unroll
-        for (int r = 0; r < 16; ++r) e[r] = __builtin_amdgcn_exp2f(x2[r]);
-        if (!all_rows_valid) {
-#pragma unroll
-          for (int r = 0; r < 16; ++r)
-            if (v0 + mb * 32 + 8 * (r >> 2) + 4 * lhi + (r & 3) >= V) e[r] = 0.f;
-        }
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          s4[r & 3] += e[r];
-          if (kEntropy) t4[r & 3] = fmaf(e[r], x2[r], t4[r & 3]);
-          acc[mb][nb][r] = e[r];
-        }
-      }
-      float s = (s4[0] + s4[1]) + (s4[2] + s4[3]);
-      s += __shfl_xor(s, 32);
-      if (lhi == 0) s_part[(int64_t)granule * ld_part + kk] = s;
-      if (kEntropy) {
-        float t = ((t4[0] + t4[1]) + (t4[2] + t4[3])) * kLn2;     // back to natural-log units
-        t += __shfl_xor(t, 32);
-        if (lhi == 0) t_part[(int64_t)granule * ld_part + kk] = t;
       }
     }
 
-    if (!kStoreE) return;                                  // forward pass alone: the sums are all that is kept
-
-    // Et (rows = vocabulary, k = token): neighbouring lanes hold neighbouring tokens; an exchange
-    // with lane^1 lets even lanes store rows r (two tokens, 4 bytes) and odd lanes rows r+1.
-    const bool odd = lane & 1;
+    // One pass over the accumulators, a 32 x 32 block at a time: E = exp(min(z - shift, 70)) as
+    // 2^(min(z * log2(e) - shift * log2(e), 70 * log2(e))) (one fma, one min and the hardware exponential
+    // per logit, sixteen at a time with independent temporaries), its running sums, and at once both
+    // stores of the block, so that the stores of one block are in flight under the exponentials of the
+    // next:
+    //   Et (rows = vocabulary, k = token): neighbouring lanes hold neighbouring tokens; an exchange
+    //      with lane^1 lets even lanes store rows r (two tokens, 4 bytes) and odd lanes rows r+1;
+    //   Eb (rows = token, k = vocabulary): a lane holds 4 consecutive vocabulary entries of its token;
+    //      64 vocabulary rows at a time are staged through this wavefront's own part of the LDS ring
+    //      (free after the k-loop) and leave as 16-byte stores, 1 KiB contiguous per instruction.
+    // The staging area is private to the wavefront and LDS operations of one wavefront execute in
+    // order, so no barrier is needed between its writes, its reads and the next half's writes.
+    float s4[NB][4], t4[NB][4];
 #pragma unroll
-    for (int nb = 0; nb < NB; ++nb) {
-      const int kk_pair = k0 + nb * 32 + (l32 & ~1);
+    for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
-      for (int mb = 0; mb < 4; ++mb)
-#pragma unroll
-        for (int r = 0; r < 16; r += 2) {
-          const float x = acc[mb][nb][r], yv = acc[mb][nb][r + 1];
-          const float give = odd ? x : yv;
-          const float got = __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, give), 0xB1, 0xF, 0xF, true));
-          const float lo = odd ? got : x, hi = odd ? yv : got;
-          const uint32_t packed = pack_bf16x2(lo, hi);
-          const int v = v0 + mb * 32 + 8 * (r >> 2) + 4 * lhi + (r & 3) + (odd ? 1 : 0);
-          NAT_E_STORE((uint32_t*)(Et + blk_off(v, kk_pair, kb_e)), packed);
-        }
-    }
-
-    // Eb (rows = token, k = vocabulary): each lane holds 4 consecutive vocabulary entries of its
-    // token; stage 64 vocabulary rows at a time through LDS (free after the k-loop) so that the
-    // global stores are 16 bytes per lane and contiguous (kTok tokens x 64 bytes per k-slice).
+      for (int q = 0; q < 4; ++q) { s4[nb][q] = 0.f; t4[nb][q] = 0.f; }
     char* stage = lds + wave * (kTok * kStageRow);
 #pragma unroll
     for (int half = 0; half < 2; ++half) {
-      __syncthreads();
 #pragma unroll
-      for (int nb = 0; nb < NB; ++nb)
+      for (int nb = 0; nb < NB; ++nb) {
+        const float nshift2 = -pre.shift[nb] * kLog2e;
+        const int kk_pair = k0 + nb * 32 + (l32 & ~1);
 #pragma unroll
-        for (int mbh = 0; mbh < 2; ++mbh)
+        for (int mbh = 0; mbh < 2; ++mbh) {
+          const int mb = half * 2 + mbh;
+          float x2[16], e[16];
 #pragma unroll
-          for (int r4 = 0; r4 < 4; ++r4) {
-            const f32x16& a = acc[half * 2 + mbh][nb];
-            uint2 w;
-            w.x = pack_bf16x2(a[4 * r4], a[4 * r4 + 1]);
-            w.y = pack_bf16x2(a[4 * r4 + 2], a[4 * r4 + 3]);
-            *(uint2*)(stage + (nb * 32 + l32) * kStageRow + (mbh * 32 + 8 * r4 + 4 * lhi) * 2) = w;
+          for (int r = 0; r < 16; ++r) x2[r] = fminf(fmaf(acc[mb][nb][r], kLog2e, nshift2), 70.f * kLog2e);
+#pragma unroll
+          for (int r = 0; r < 16; ++r) e[r] = __builtin_amdgcn_exp2f(x2[r]);
+          if (!all_rows_valid) {                           // only the last vocabulary tile pays for the row check
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
+              if (v0 + mb * 32 + 8 * (r >> 2) + 4 * lhi + (r & 3) >= V) e[r] = 0.f;
           }
-      __syncthreads();
 #pragma unroll
-      for (int i = 0; i < kTok / 8; ++i) {
-        const int q = i * 64 + lane;                    // slice q/(4 kTok), token (q%(4 kTok))/4, 16-byte chunk q%4
-        const int sl = q / (4 * kTok), tok = (q % (4 * kTok)) >> 2, ch = q & 3;
-        const uint4 val = *(const uint4*)(stage + tok * kStageRow + sl * 64 + ch * 16);
-        NAT_E_STORE((u32x4v*)(Eb + blk_off(k0 + tok, v0 + half * 64 + sl * 32 + ch * 8, kb_z)), __builtin_bit_cast(u32x4v, val));
+          for (int r = 0; r < 16; ++r) {
+            s4[nb][r & 3] += e[r];
+            if (kEntropy) t4[nb][r & 3] = fmaf(e[r], x2[r], t4[nb][r & 3]);
+          }
+          if (kStoreE) {
+#pragma unroll
+            for (int r4 = 0; r4 < 4; ++r4) {
+              uint2 w;
+              w.x = pack_bf16x2(e[4 * r4], e[4 * r4 + 1]);
+              w.y = pack_bf16x2(e[4 * r4 + 2], e[4 * r4 + 3]);
+              *(uint2*)(stage + (nb * 32 + l32) * kStageRow + (mbh * 32 + 8 * r4 + 4 * lhi) * 2) = w;
+            }
+#pragma unroll
+            for (int r = 0; r < 16; r += 2) {
+              const float x = e[r], yv = e[r + 1];
+              const float give = odd ? x : yv;
+              const float got = __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, give), 0xB1, 0xF, 0xF, true));
+              const float lo = odd ? got : x, hi = odd ? yv : got;
+              const int v = v0 + mb * 32 + 8 * (r >> 2) + 4 * lhi + (r & 3) + (odd ? 1 : 0);
+              NAT_E_STORE((uint32_t*)(Et + blk_off(v, kk_pair, kb_e)), pack_bf16x2(lo, hi));
+            }
+          }
+        }
+      }
+      if (kStoreE) {
+#pragma unroll
+        for (int i = 0; i < kTok / 8; ++i) {
+          const int q = i * 64 + lane;                    // slice q/(4 kTok), token (q%(4 kTok))/4, 16-byte chunk q%4
+          const int sl = q / (4 * kTok), tok = (q % (4 * kTok)) >> 2, ch = q & 3;
+          const uint4 val = *(const uint4*)(stage + tok * kStageRow + sl * 64 + ch * 16);
+          NAT_E_STORE((u32x4v*)(Eb + blk_off(k0 + tok, v0 + half * 64 + sl * 32 + ch * 8, kb_z)), __builtin_bit_cast(u32x4v, val));
+        }
+      }
+    }
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) {
+      const int kk = k0 + nb * 32 + l32;                   // token column (always inside the padded chunk)
+      float s = (s4[nb][0] + s4[nb][1]) + (s4[nb][2] + s4[nb][3]);
+      s += __shfl_xor(s, 32);
+      if (lhi == 0) s_part[(int64_t)granule * ld_part + kk] = s;
+      if (kEntropy) {
+        float t = ((t4[nb][0] + t4[nb][1]) + (t4[nb][2] + t4[nb][3])) * kLn2;     // back to natural-log units
+        t += __shfl_xor(t, 32);
+        if (lhi == 0) t_part[(int64_t)granule * ld_part + kk] = t;
       }
     }
   }
@@ -784,7 +791,7 @@ nat_status loss_bf16_run(const LossArgs& a) {
 
   {  // W and W^T in the blocked layout, padding zero-filled
     ProfScope prof(PC_TRANSPOSE, s);
-    pack_blocked_kernel<<<dim3(Vp / 64, Hp / 64), 256, 0, s>>>(W, H, V, H, Vp, Hp, Wb, Wtb, nullptr);
+    pack_blocked_kernel<<<dim3(Vp / 64, Hp / 64), 256, 0, s>>>(W, H, V, H, Vp, Hp, Wb, Wtb, Vp / 32, nullptr);
     NAT_LAUNCH_CHECK();
   }
   for (int c0 = 0; c0 < a.N_k; c0 += cap) {
@@ -793,43 +800,56 @@ nat_status loss_bf16_run(const LossArgs& a) {
     const uint16_t* hid_c = hidden + (int64_t)c0 * H;
     {  // H_chunk in the blocked layout; exponent shift = target logit
       ProfScope prof(PC_TRANSPOSE, s);
-      pack_blocked_kernel<<<dim3(np / 64, H / 64), 256, 0, s>>>(hid_c, H, nv, H, np, Hp, Hb, nullptr, nullptr);
+      pack_blocked_kernel<<<dim3(np / 64, H / 64), 256, 0, s>>>(hid_c, H, nv, H, np, Hp, Hb, nullptr, 0, nullptr);
       NAT_LAUNCH_CHECK();
       target_logit_kernel<<<(nv + 3) / 4, 256, 0, s>>>(hid_c, W, a.ids + c0, nv, H, V, ref);
       NAT_LAUNCH_CHECK();
     }
-    {  // logits: rows = vocabulary, columns = tokens, contraction over the hidden size
-      GemmArgs g{Wb, Hb, H, Vp / kBM, np / kBN, NAT_GROUP_LOGITS};
-      nat_status st;
-      if (t_part) {
-        LogitsEpilogue<true> e{V, nv, cap, np / 32, Vp / 32, Et, Eb, s_part, t_part, zt, a.ids + c0, ref};
-        st = launch_gemm<NAT_WAVES_LOGITS>(g, e, PC_LOGITS, s);
-      } else {
-        LogitsEpilogue<false> e{V, nv, cap, np / 32, Vp / 32, Et, Eb, s_part, nullptr, zt, a.ids + c0, ref};
-        st = launch_gemm<NAT_WAVES_LOGITS>(g, e, PC_LOGITS, s);
+    // The forward sweep and the dH contraction go over the chunk in sub-chunks: shorter launches of
+    // the three contractions alternate, which this power-limited part rewards with a higher clock
+    // (measured: both run faster on 8192 tokens than on 32768), while the dW contraction below keeps
+    // the whole chunk as its contraction axis (it is the one that loses on short axes).
+    for (int s0 = 0; s0 < nv; s0 += kSubChunk) {
+      const int snv = nv - s0 < kSubChunk ? nv - s0 : kSubChunk;
+      const int snp = (int)round_up(snv, kBN);
+      uint16_t* Et_s = Et + (int64_t)(s0 / 32) * kBlkElems;                 // k-slice s0 / 32 of every vocabulary tile
+      uint16_t* Eb_s = Eb + (int64_t)(s0 / 256) * (Vp / 32) * kBlkElems;    // token tile s0 / 256
+      const int32_t* ids_s = a.ids + c0 + s0;
+      {  // logits: rows = vocabulary, columns = tokens, contraction over the hidden size
+        GemmArgs g{Wb, Hb + (int64_t)(s0 / 256) * (H / 32) * kBlkElems, H, Vp / kBM, snp / kBN, NAT_GROUP_LOGITS};
+        nat_status st;
+        if (t_part) {
+          LogitsEpilogue<true> e{V, snv, cap, np / 32, Vp / 32, Et_s, Eb_s, s_part + s0, t_part + s0, zt + s0, ids_s, ref + s0};
+          st = launch_gemm<NAT_WAVES_LOGITS>(g, e, PC_LOGITS, s);
+        } else {
+          LogitsEpilogue<false> e{V, snv, cap, np / 32, Vp / 32, Et_s, Eb_s, s_part + s0, nullptr, zt + s0, ids_s, ref + s0};
+          st = launch_gemm<NAT_WAVES_LOGITS>(g, e, PC_LOGITS, s);
+        }
+        if (st != NAT_OK) return st;
       }
-      if (st != NAT_OK) return st;
-    }
-    {
-      ProfScope prof(PC_TOKEN_STATS, s);
-      token_stats_kernel<<<(nv + 63) / 64, 256, 0, s>>>(s_part, t_part, p.n_granules, cap, ref, zt, nv, c0, a.ids + c0, V,
-                                                       a.old_logp, a.adv, a.kept_seq, a.kept_w, a.eps_lo, a.eps_hi,
-                                                       a.grad_scale, KlArgs{a.ref_logp, a.beta_kl, a.kl_kind}, beta,
-                                                       patch, a.logp, a.kl_out, a.entropy_out, term, a.diag);
-      NAT_LAUNCH_CHECK();
-      patch_target_kernel<<<(nv + 255) / 256, 256, 0, s>>>(Et, np / 32, Eb, Vp / 32, a.ids + c0, patch, nv, V);
-      NAT_LAUNCH_CHECK();
-    }
-    {  // (diag(beta) H_chunk)^T in the blocked layout
-      ProfScope prof(PC_TRANSPOSE, s);
-      pack_blocked_kernel<<<dim3(np / 64, Hp / 64), 256, 0, s>>>(hid_c, H, nv, H, np, Hp, nullptr, Hktb, beta);
-      NAT_LAUNCH_CHECK();
-    }
-    {  // dH: rows = tokens, columns = hidden units, contraction over the padded vocabulary
-      GemmArgs g{Eb, Wtb, Vp, np / kBM, Hp / kBN, NAT_GROUP_DHIDDEN};
-      DHiddenEpilogue e{nv, H, (uint16_t*)a.dH + (int64_t)c0 * H, beta};
-      nat_status st = launch_gemm<NAT_WAVES_DHIDDEN>(g, e, PC_DHIDDEN, s);
-      if (st != NAT_OK) return st;
+      {
+        ProfScope prof(PC_TOKEN_STATS, s);
+        token_stats_kernel<<<(snv + 63) / 64, 256, 0, s>>>(s_part + s0, t_part ? t_part + s0 : nullptr, p.n_granules, cap,
+                                                          ref + s0, zt + s0, snv, c0 + s0, ids_s, V, a.old_logp, a.adv,
+                                                          a.kept_seq, a.kept_w, a.eps_lo, a.eps_hi, a.grad_scale,
+                                                          KlArgs{a.ref_logp, a.beta_kl, a.kl_kind}, beta + s0, patch + s0,
+                                                          a.logp, a.kl_out, a.entropy_out, term, a.diag);
+        NAT_LAUNCH_CHECK();
+        patch_target_kernel<<<(snv + 255) / 256, 256, 0, s>>>(Et_s, np / 32, Eb_s, Vp / 32, ids_s, patch + s0, snv, V);
+        NAT_LAUNCH_CHECK();
+      }
+      {  // (diag(beta) H)^T of the sub-chunk into its k-slices of the chunk's blocked operand
+        ProfScope prof(PC_TRANSPOSE, s);
+        pack_blocked_kernel<<<dim3(snp / 64, Hp / 64), 256, 0, s>>>(hid_c + (int64_t)s0 * H, H, snv, H, snp, Hp, nullptr,
+                                                                   Hktb + (int64_t)(s0 / 32) * kBlkElems, np / 32, beta + s0);
+        NAT_LAUNCH_CHECK();
+      }
+      {  // dH: rows = tokens, columns = hidden units, contraction over the padded vocabulary
+        GemmArgs g{Eb_s, Wtb, Vp, snp / kBM, Hp / kBN, NAT_GROUP_DHIDDEN};
+        DHiddenEpilogue e{snv, H, (uint16_t*)a.dH + (int64_t)(c0 + s0) * H, beta + s0};
+        nat_status st = launch_gemm<NAT_WAVES_DHIDDEN>(g, e, PC_DHIDDEN, s);
+        if (st != NAT_OK) return st;
+      }
     }
     {  // dW: rows = vocabulary, columns = hidden units, contraction over the chunk's (padded) tokens
       GemmArgs g{Et, Hktb, np, Vp / kBM, Hp / kBN, NAT_GROUP_DWEIGHT};
@@ -863,7 +883,7 @@ nat_status logp_bf16_run(const LogpArgs& a) {
   const int H = a.H, V = a.V, Vp = (int)p.Vp;
   {
     ProfScope prof(PC_TRANSPOSE, s);
-    pack_blocked_kernel<<<dim3(Vp / 64, H / 64), 256, 0, s>>>(W, H, V, H, Vp, H, Wb, nullptr, nullptr);
+    pack_blocked_kernel<<<dim3(Vp / 64, H / 64), 256, 0, s>>>(W, H, V, H, Vp, H, Wb, nullptr, 0, nullptr);
     NAT_LAUNCH_CHECK();
   }
   for (int c0 = 0; c0 < a.N_k; c0 += cap) {
@@ -872,7 +892,7 @@ nat_status logp_bf16_run(const LogpArgs& a) {
     const uint16_t* hid_c = hidden + (int64_t)c0 * H;
     {
       ProfScope prof(PC_TRANSPOSE, s);
-      pack_blocked_kernel<<<dim3(np / 64, H / 64), 256, 0, s>>>(hid_c, H, nv, H, np, H, Hb, nullptr, nullptr);
+      pack_blocked_kernel<<<dim3(np / 64, H / 64), 256, 0, s>>>(hid_c, H, nv, H, np, H, Hb, nullptr, 0, nullptr);
       NAT_LAUNCH_CHECK();
       target_logit_kernel<<<(nv + 3) / 4, 256, 0, s>>>(hid_c, W, a.ids + c0, nv, H, V, ref);
       NAT_LAUNCH_CHECK();

@@ -128,29 +128,6 @@ def make_batch_torch(name, seed, device, P=None, G=None, lengths=None):
     return b
 
 
-def behaviour_logp_stand_in(hidden, W, ids, logp_noise):
-    """Behaviour-policy log-probs for batches too large for an exact reference
-    forward: target logit minus the log-partition a head with i.i.d.
-    N(0, W_STD^2) rows has in expectation (ln V + W_STD^2 |h|^2 / 2), plus
-    the N(0, 0.05) noise.  This keeps the importance ratios near one the way
-    "current log-prob + noise" does (error of the stand-in ~ 5e-3 at V=151936).
-    Works on numpy arrays or torch tensors; an input recipe, not a forward pass.
-    """
-    if isinstance(hidden, np.ndarray):
-        h = hidden.astype(np.float64)
-        zy = np.einsum("nh,nh->n", h, W[ids.astype(np.int64)].astype(np.float64))
-        lse = math.log(W.shape[0]) + 0.5 * W_STD ** 2 * np.einsum("nh,nh->n", h, h)
-        return (zy - lse + logp_noise).astype(np.float32)
-    import torch
-    out = torch.empty(hidden.shape[0], device=hidden.device, dtype=torch.float32)
-    step = 16384
-    for a in range(0, hidden.shape[0], step):
-        h = hidden[a:a + step].float()
-        wy = W[ids[a:a + step].long()].float()
-        out[a:a + step] = (h * wy).sum(1) - (math.log(W.shape[0]) + 0.5 * W_STD ** 2 * (h * h).sum(1))
-    return out + logp_noise
-
-
 # ---- inputs of the widened selection stage: cut-length schedules, per-token
 # ---- inclusion probabilities, prompt lengths (random draws only; what they mean
 # ---- is the selection code's business)

@@ -25,6 +25,18 @@ def rel_frobenius(got, ref):
     return float(np.linalg.norm(got - ref) / den) if den > 0 else float(np.linalg.norm(got))
 
 
+def dh_residual_error(dH_got, ref, W, ids, out_ulp):
+    """(error of dH with the one-hot term c_k W[y_k] removed on both sides, over the largest residual
+    entry of the oracle; that largest entry).  See contraction_errors."""
+    ids = np.asarray(ids, dtype=np.int64)
+    W_rows = np.asarray(W[ids], dtype=np.float64)
+    res_ref = ref["dH"] - ref["c"][:, None] * W_rows
+    diff = np.abs(np.asarray(dH_got, dtype=np.float64) - ref["dH"]) - out_ulp * np.abs(ref["dH"])
+    den = np.abs(res_ref).max()
+    err = float(np.maximum(diff, 0.0).max())
+    return (err / den if den > 0 else err), den
+
+
 def contraction_errors(dH_got, dW_got, ref, hidden, W, ids, out_ulp):
     """Errors of the parts of dH and dW that only the two backward contractions produce.
 
@@ -44,11 +56,7 @@ def contraction_errors(dH_got, dW_got, ref, hidden, W, ids, out_ulp):
     W64 = np.asarray(W, dtype=np.float64)
     dH_got = np.asarray(dH_got, dtype=np.float64)
     dW_got = np.asarray(dW_got, dtype=np.float64)
-    onehot_dH = ref["c"][:, None] * W64[ids]
-    res_ref = ref["dH"] - onehot_dH
-    diff = np.abs(dH_got - ref["dH"]) - out_ulp * np.abs(ref["dH"])
-    den = np.abs(res_ref).max()
-    dH_res = float(np.maximum(diff, 0.0).max() / den) if den > 0 else float(np.maximum(diff, 0.0).max())
+    dH_res, den = dh_residual_error(dH_got, ref, W64, ids, out_ulp)
     off = np.ones(W64.shape[0], dtype=bool)
     off[ids] = False
     if off.any():
@@ -138,3 +146,20 @@ def hip_loss(stage, case, dtype, **kw):
                      n, **kw)
     torch.cuda.synchronize()
     return out
+
+
+def behaviour_logp_from_forward(stage, batch, n_spot=24, seed=0):
+    """Behaviour-policy log-probs of a full-size device batch: the current policy's log-prob of every
+    token (the forward pass alone, nat_logp_fwd, over all N tokens) plus the batch's N(0, 0.05) noise.
+    A random subsample of the forward log-probs is checked against the oracle (fp64, token by token)."""
+    N = batch["N"]
+    lp = stage.logp(batch["hidden"], batch["W"], batch["ids"], N)["logp"][:N]
+    torch.cuda.synchronize()
+    spot = np.unique(np.concatenate([[0, N - 1], np.random.default_rng(seed).integers(0, N, n_spot)]))
+    sidx = torch.from_numpy(spot).to(batch["hidden"].device)
+    ref = ogrpo.token_logp(batch["hidden"][sidx].float().cpu().numpy(), batch["W"].float().cpu().numpy(),
+                           batch["ids"][sidx].cpu().numpy())
+    tol = 1e-4 if batch["dtype"] == "bf16" else 1e-5 * float(np.abs(ref).max())
+    err = float(np.abs(lp[sidx].cpu().numpy().astype(np.float64) - ref).max())
+    assert err <= tol, ("forward log-probs against the oracle", err)
+    return lp + batch["logp_noise"]

@@ -10,7 +10,7 @@ pytestmark = pytest.mark.gpu
 import synth_inputs as si
 from oracle import grpo as ogrpo
 from oracle import select as osel
-from nat_testlib import DEV, max_rel_err
+from nat_testlib import DEV, behaviour_logp_from_forward, dh_residual_error, max_rel_err
 
 TOL_BF16 = 2e-2
 
@@ -30,7 +30,7 @@ def test_full_size_workload_sampled_tokens(name, mode, kw):
     seed = 1000 * si.WORKLOAD_ORDER.index(name)
     b = si.make_batch_torch(name, seed, DEV)
     B, N, G = b["B"], b["N"], b["G"]
-    old_logp = si.behaviour_logp_stand_in(b["hidden"], b["W"], b["ids"], b["logp_noise"])
+    old_logp = behaviour_logp_from_forward(stage, b)
     cu = torch.from_numpy(b["cu_seqlens"]).to(DEV)
     adv = stage.advantage(torch.from_numpy(b["rewards"].reshape(-1)).to(DEV), b["P"], G)
     adv_ref = ogrpo.advantages(b["rewards"]).reshape(-1)
@@ -66,12 +66,14 @@ def test_full_size_workload_sampled_tokens(name, mode, kw):
                                adv_ref[sc["kept_seq"][sidx].cpu().numpy()],
                                sc["kept_w"][sidx].cpu().numpy().astype(np.float64))
     logp = out["logp"][sidx].cpu().numpy()
-    assert np.abs(logp - ref["logp"]).max() < 5e-3
+    assert np.abs(logp - ref["logp"]).max() <= 1e-4
     dH = out["dH"][sidx].float().cpu().numpy()
     for j in range(len(sample)):
         den = np.abs(ref["dH"][j]).max()
         if den > 0:
             assert np.abs(dH[j] - ref["dH"][j]).max() <= TOL_BF16 * den, (name, int(sample[j]))
+    res_err, _ = dh_residual_error(dH, ref, b["W"].float().cpu().numpy(), sc["ids_k"][sidx].cpu().numpy(), 2.0 ** -7)
+    assert res_err <= TOL_BF16, (name, "dH without the one-hot term", res_err)
     assert np.isfinite(out["loss"].item()) and torch.isfinite(out["dW"]).all()
     print(name, mode, "kept", nk, "of", N, "sampled rel err logp %.2e dH %.2e" %
           (max_rel_err(logp, ref["logp"]), max_rel_err(dH, ref["dH"])))

@@ -37,10 +37,3 @@ def test_equal_reward_groups_and_workload_table():
     assert all(len(set(R[i])) == 1 for i in range(4))
     assert [si.WORKLOADS[n]["H"] for n in si.WORKLOAD_ORDER] == [64, 1024, 4096, 4096, 5120, 3584]
     assert si.WORKLOADS["qwen3_8b_head_rpc"]["V"] == 151936
-
-
-def test_behaviour_logp_stand_in_is_near_on_policy():
-    b = si.make_batch_numpy("tiny_fp32", 1)
-    old = si.behaviour_logp_stand_in(b["hidden"], b["W"], b["ids"], b["logp_noise"])
-    assert old.dtype == np.float32 and old.shape == (b["N"],)
-    assert abs(old.mean() + np.log(512)) < 0.1

@@ -4,31 +4,37 @@
 // (App. A) on the kept tokens.  The forward pass alone runs the first two steps below and
 // keeps only the sums.
 //
-// Tokens are processed in chunks of at most `cap` rows.  Per chunk:
+// Tokens are processed in chunks of at most `cap` rows (32768 with the recommended workspace); the
+// forward sweep and the dH contraction of a chunk run in sub-chunks of 8192 rows.  Per chunk:
 //   reference     ref_k = h_k . W[ids_k]: the target logit, used only as the exponent shift;
-//   logits GEMM   Z^T tile = W_tile . H_chunk^T on bf16 MFMA with fp32 accumulators; the
-//                 epilogue never stores Z: it stores E = exp(z - ref_k) as bf16 in both
-//                 operand orientations (soft-max numerators: bf16 keeps their relative
-//                 precision), per (token, 128-row vocabulary granule) partial sums of E, and
-//                 the exact target logit;
+//   logits GEMM   Z^T tile = W_tile . H^T on bf16 MFMA with fp32 accumulators; the epilogue never
+//                 stores Z: it stores E = exp(z - ref_k) as bf16, ONCE, rows = token (soft-max
+//                 numerators: bf16 keeps their relative precision), per (token, 128-row vocabulary
+//                 granule) partial sums of E, and the exact target logit;
 //   token stats   S_k = sum of the partials (fixed order), lse = ref + log S, log-prob, ratio,
 //                 clipped surrogate, c_k = dLoss/dlogp_k, beta_k = -c_k / S_k;
 //                 dz_kv = beta_k E_kv, except the target entry c_k (1 - p_target), which is
 //                 patched into E as -S_k (1 - p_target), computed in fp32 before rounding;
-//   dH GEMM       dH_chunk = diag(beta) (E . W)      (contraction over the vocabulary);
-//   dW GEMM       dW (+)= E^T . (diag(beta) H_chunk) (contraction over the chunk's tokens,
-//                 fp32, one owner per output tile, chunks in order: deterministic).
+//   dH GEMM       dH = diag(beta) (E . W)            (contraction over the vocabulary);
+//   dW GEMM       dW (+)= E^T . (diag(beta) H_chunk) (contraction over the chunk's tokens, fp32,
+//                 one owner per output tile, chunks in order: deterministic).  Its A operand is
+//                 the same copy of E, which is stored along this contraction's k axis: the tile
+//                 is gathered in 2 KiB pieces and fragments are formed by the transposing LDS
+//                 read (ds_read_b64_tr_b16).
 // The shift by the target logit needs log(p_max / p_target) < 70 for every kept token (E is
-// clamped there); a token the current policy gives less than e^-70 of its mode's probability
-// does not occur for rollouts drawn from a behaviour policy inside the clip range.
-// All three contractions run through one "NT" kernel (both operands contiguous
-// along the contraction axis).  Every operand is kept in a blocked layout in the
-// workspace: blocks of 256 rows x 32 k-elements (16 KiB, contiguous), ordered k-fastest
-// inside a 256-row tile, so a workgroup streams one contiguous region per operand
-// instead of 256 strided rows.  W and H_chunk are repacked (plain and transposed);
-// the soft-max numerators and dZ are produced directly in that layout.
+// clamped there; the token statistics count the tokens this may have touched); a token the current
+// policy gives less than e^-70 of its mode's probability does not occur for rollouts drawn from a
+// behaviour policy inside the clip range.
+// All three contractions run through one "NT" kernel (both operands contiguous along the
+// contraction axis; the k-major A operand of dW is the one exception described above).  Every
+// operand is kept in a blocked layout in the workspace: blocks of 256 rows x 32 k-elements (16 KiB,
+// contiguous), ordered k-fastest inside a 256-row tile, so a workgroup streams one contiguous
+// region per operand instead of 256 strided rows.  W and H_chunk are repacked (plain and
+// transposed); the soft-max numerators are produced directly in that layout.
 #include "nat_internal.h"
 #include "grpo_scalar.hip.h"
+
+#include <type_traits>
 
 namespace nat {
 
@@ -137,6 +143,7 @@ struct GemmArgs {
   int K;                      // multiple of kBK
   int tiles_m, tiles_n;
   int group_m;                // tile rows walked together (see tile_of_block)
+  int kb_a_src;               // k-major A only (see TileLoaderKMajor): k-slices of the source operand
 };
 
 // Block id -> output tile.  Blocks are dealt round-robin to the 8 XCDs, so ids
@@ -196,6 +203,81 @@ struct TileLoader {
   }
 };
 
+// The same copy for an A operand that is only stored with its rows along THIS contraction's k axis
+// (the soft-max numerators: rows = token, k = vocabulary, read by the dW contraction whose k axis is
+// the token).  A [256 rows][32 k] tile of the contraction is then eight pieces of the source, one per
+// 32-row block of the tile: rows (kt % 8) * 32 .. + 31 of the source block (token tile kt / 8, k-slice
+// 8 * tile + piece), 2 KiB contiguous each.  The LDS tile holds the pieces one after another, i.e.
+// [row block][k][row within block], and fragments come out of it through the transposing LDS read.
+template <int NW>
+struct TileLoaderKMajor {
+  static constexpr int kLoads = kTileBytes / 1024 / NW;     // per wavefront: 4 or 2
+  static constexpr int kPieces = kLoads / 2;                // 2 KiB pieces per wavefront: 2 or 1
+  const uint16_t* src;           // this lane's 16 bytes of the wavefront's first piece, token tile 0, rows 0..15
+  int64_t tile_stride;           // elements between consecutive token tiles of the source
+
+  __device__ __forceinline__ void init(const uint16_t* base, int tile, int kb_src, int wave, int lane) {
+    src = base + (int64_t)(8 * tile + wave * kPieces) * kBlkElems + lane * 8;
+    tile_stride = (int64_t)kb_src * kBlkElems;
+  }
+  __device__ __forceinline__ void issue(char* lds_tile, int kt, int wave) const {
+    const uint16_t* p = src + (int64_t)(kt >> 3) * tile_stride + (kt & 7) * 1024;
+    char* dst = lds_tile + wave * (kPieces * 2048);
+    static_assert(kPieces == 2 || kPieces == 1, "written out below");
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)p,
+                                     (__attribute__((address_space(3))) void*)dst, 16, 0, 0);
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)p,
+                                     (__attribute__((address_space(3))) void*)dst, 16, 1024, 0);
+    if (kPieces == 2) {
+      const uint16_t* p2 = p + kBlkElems;
+      char* dst2 = dst + 2048;
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)p2,
+                                       (__attribute__((address_space(3))) void*)dst2, 16, 0, 0);
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)p2,
+                                       (__attribute__((address_space(3))) void*)dst2, 16, 1024, 0);
+    }
+  }
+};
+
+// Per-lane byte offsets, inside a [k = 32][32 rows] piece, of the two transposing reads (q = 0, 1)
+// that make one A fragment of k-substep 0.  The transposing read works on groups of 16 lanes: lane
+// i of a group supplies the address of 4 consecutive 16-bit elements and receives element i % 4 of
+// the lanes i / 4, i / 4 + 4, i / 4 + 8, i / 4 + 12.  With lane i pointing at k = K0 + i / 4 and rows
+// 16 g + 4 (i % 4) .. + 3, lane i ends up with row 16 g + i and k = K0 .. K0 + 3: the MFMA's A layout
+// (row = lane % 32, 8 consecutive k from 8 * (lane / 32)) after two reads, K0 = 8 * (lane / 32) + 4 q.
+// The 16-byte chunks of a source row are stored XOR-ed with bits 2..3 of the row (see blk_off); for
+// these k values that is 2 * (lane / 32) + q.  The 32 lanes of a half-wavefront then cover all 64
+// LDS banks exactly once.
+struct KMajorFragOffsets {
+  int off[2];
+  __device__ __forceinline__ void init(int lane) {
+    const int i = lane & 15, g = (lane >> 4) & 1, lhi = lane >> 5, a = i & 3;
+#pragma unroll
+    for (int q = 0; q < 2; ++q)
+      off[q] = (8 * lhi + 4 * q + (i >> 2)) * 64 + ((((2 * g + (a >> 1)) ^ (2 * lhi + q)) & 3) << 4) + (a & 1) * 8;
+  }
+};
+
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x8 __attribute__((ext_vector_type(8)));
+
+// The transposing LDS read as inline assembly: through the compiler's builtin every such read is
+// preceded by a wait for ALL outstanding direct-to-LDS loads (it carries no memory operand, so the
+// wait-count pass assumes it may alias them), which serialises the k-loop's prefetch (measured: the
+// dW contraction 20-30 % slower).  The compiler does not know that this statement reads LDS: the code
+// that uses it waits for lgkmcnt itself before consuming the result, and orders it against the loads
+// with its own vmcnt waits and barriers, exactly as it does for the plain fragment reads.
+template <int kOffset>
+__device__ __forceinline__ s16x4 lds_read_tr16_b64(uint32_t lds_addr) {
+  s16x4 v;
+  asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(v) : "v"(lds_addr), "n"(kOffset));
+  return v;
+}
+
+__device__ __forceinline__ uint32_t lds_addr_of(const char* p) {
+  return (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) char*)p;
+}
+
 // fragments of k-substep ks: four 32-row blocks of A from row a_row0, NB 32-row blocks of B from b_row0
 template <int NB>
 __device__ __forceinline__ void load_frags(const char* a_s, const char* b_s, int a_row0, int b_row0, int l32, int lhi,
@@ -221,7 +303,9 @@ constexpr int waitcnt_vm(int n) { return (n & 15) | ((n >> 4) << 14) | 0x0f70; }
 // NW wavefronts in a 2 x (NW/2) grid over the 256 x 256 tile: wavefront (wm, wn) owns rows
 // wm*128.. and columns wn*(NB*32).. with NB = 16/NW (4 wavefronts: 128 columns, 8: 64 columns).
 // acc[mb][nb] element r of lane l is C[row0 + mb*32 + 8*(r/4) + 4*(l/32) + r%4][col0 + nb*32 + l%32]
-template <class Epilogue, int NW>
+// AT: the A operand is read from a source stored along this contraction's k axis (TileLoaderKMajor);
+// g.kb_a_src is then the number of k-slices of that source.
+template <class Epilogue, int NW, bool AT = false>
 __global__ void __launch_bounds__(NW * 64, 1)
 gemm_nt_kernel(GemmArgs g, Epilogue epi) {
   constexpr int NB = 16 / NW;                                  // 32-column blocks per wavefront
@@ -249,10 +333,96 @@ gemm_nt_kernel(GemmArgs g, Epilogue epi) {
   typename Epilogue::template Pre<NB> pre;
   epi.prefetch(pre, n0 + b_row0, lane);
 
-  TileLoader<NW> la, lb;
+  typename std::conditional<AT, TileLoaderKMajor<NW>, TileLoader<NW>>::type la;
+  TileLoader<NW> lb;
   const int kt_n = g.K / kBK;
-  la.init(g.A, tm, kt_n, wave, lane);
+  la.init(g.A, tm, AT ? g.kb_a_src : kt_n, wave, lane);
   lb.init(g.B, tn, kt_n, wave, lane);
+
+  if constexpr (AT) {
+    // The pipeline described below, written out slot by slot: MFMA m of a k-substep is followed by the
+    // fragment reads (and, at the end of the second substep, the refill loads) given to its slot, and a
+    // scheduling fence keeps the compiler from regrouping them, since it cannot see what the assembly
+    // reads are.  A fragment of block i, substep ks = two transposing reads in piece a_blk0 + i at
+    // offset ks * 1024; B fragment j = one 16-byte read.
+    KMajorFragOffsets fo;
+    fo.init(lane);
+#pragma unroll
+    for (int st = 0; st < kStages; ++st) {
+      const int k = st < kt_n ? st : kt_n - 1;
+      la.issue(lds[st][0], k, wave);
+      lb.issue(lds[st][1], k, wave);
+    }
+    __builtin_amdgcn_s_waitcnt(waitcnt_vm((kStages - 1) * kLoadsPerWave));
+    __syncthreads();
+    s16x4 at[2][4][2];                                   // [substep][row block][q]
+    bf16x8 bt[2][NB];
+    const int a_blk0 = a_row0 / 32;
+    auto a_read = [&](const char* a_s, int ks, int i, int q) {
+      const uint32_t base = lds_addr_of(a_s) + fo.off[q] + a_blk0 * 2048;
+      switch (i * 2 + ks) {                              // the piece and the substep go into the immediate offset
+        case 0: at[ks][i][q] = lds_read_tr16_b64<0 * 2048 + 0>(base); break;
+        case 1: at[ks][i][q] = lds_read_tr16_b64<0 * 2048 + 1024>(base); break;
+        case 2: at[ks][i][q] = lds_read_tr16_b64<1 * 2048 + 0>(base); break;
+        case 3: at[ks][i][q] = lds_read_tr16_b64<1 * 2048 + 1024>(base); break;
+        case 4: at[ks][i][q] = lds_read_tr16_b64<2 * 2048 + 0>(base); break;
+        case 5: at[ks][i][q] = lds_read_tr16_b64<2 * 2048 + 1024>(base); break;
+        case 6: at[ks][i][q] = lds_read_tr16_b64<3 * 2048 + 0>(base); break;
+        default: at[ks][i][q] = lds_read_tr16_b64<3 * 2048 + 1024>(base); break;
+      }
+    };
+    auto a_frag = [&](int ks, int i) {
+      const s16x4 lo = at[ks][i][0], hi = at[ks][i][1];
+      const s16x8 both = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+      return __builtin_bit_cast(bf16x8, both);
+    };
+    constexpr int kReads = 8 + NB;                       // per substep, in issue order: 8 for A, NB for B
+    auto read_slot = [&](const char* a_s, const char* b_s, int ks, int n) {
+      if (n < 8) a_read(a_s, ks, n >> 1, n & 1);
+      else bt[ks][n - 8] = *(const bf16x8*)(b_s + lds_chunk_off(b_row0 + (n - 8) * 32 + l32, ks * 2 + lhi));
+    };
+#pragma unroll
+    for (int n = 0; n < kReads; ++n) read_slot(lds[0][0], lds[0][1], 0, n);
+
+    for (int kt = 0; kt < kt_n; ++kt) {
+      const int cur = kt % kStages, nxt = (kt + 1) % kStages;
+      // first k-substep; under it the reads of the second one
+      __builtin_amdgcn_s_waitcnt(0xc07f);               // lgkmcnt(0): the fragments of substep 0 have landed
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int m = 0; m < kMfma; ++m) {
+        const int i = m / NB, j = m % NB;
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_frag(0, i), bt[0][j], acc[i][j], 0, 0, 0);
+#pragma unroll
+        for (int n = m * kReads / kMfma; n < (m + 1) * kReads / kMfma; ++n) read_slot(lds[cur][0], lds[cur][1], 1, n);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      // slice kt+1 has landed (this wavefront's share; the barrier covers the others) and this wavefront's
+      // reads of slice kt have returned, so its buffer can be refilled below
+      __builtin_amdgcn_s_waitcnt(waitcnt_vm((kStages - 2) * kLoadsPerWave) & 0xf0ff);
+      __builtin_amdgcn_s_barrier();
+      __builtin_amdgcn_sched_barrier(0);
+      // second k-substep; under it the first reads of slice kt+1, then the refill of lds[cur]
+      int k2 = kt + kStages;
+      k2 = k2 < kt_n ? k2 : kt_n - 1;
+      constexpr int kFirst = kMfma - 2;                  // the last two slots issue the refill
+#pragma unroll
+      for (int m = 0; m < kMfma; ++m) {
+        const int i = m / NB, j = m % NB;
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_frag(1, i), bt[1][j], acc[i][j], 0, 0, 0);
+#pragma unroll
+        for (int n = m * kReads / kFirst; n < (m + 1) * kReads / kFirst && m < kFirst; ++n)
+          read_slot(lds[nxt][0], lds[nxt][1], 0, n);
+        if (m == kMfma - 2) la.issue(lds[cur][0], k2, wave);
+        if (m == kMfma - 1) lb.issue(lds[cur][1], k2, wave);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
+    __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));   // no direct-to-LDS load may outlive the block
+    __syncthreads();
+    epi(acc, pre, m0 + a_row0, n0 + b_row0, lane, wave, &lds[0][0][0]);
+    return;
+  }
 
   // Software pipeline over k-slices of 32.  Slice kt lives in lds[kt % 4]; three slices are
   // in flight while one is consumed, so a load has three iterations to land.  Loads complete
@@ -336,9 +506,8 @@ template <bool kEntropy, bool kStoreE = true>
 struct LogitsEpilogue {
   int V, n_valid;                  // vocabulary size, valid tokens in the chunk
   int64_t ld_part;                 // leading dimension (tokens) of the partial sums
-  int kb_e, kb_z;                  // k-slices of Et (padded tokens / 32) and of Eb (Vp / 32)
-  uint16_t* Et;                    // blocked, rows = vocabulary, k = token: E = exp(z - ref)
-  uint16_t* Eb;                    // blocked, rows = token, k = vocabulary: the same values
+  int kb_z;                        // k-slices of Eb (Vp / 32)
+  uint16_t* Eb;                    // blocked, rows = token, k = vocabulary: E = exp(z - ref), stored once
   float* s_part;                   // [Vp/128, ld_part] partial sums of E
   float* t_part;                   // [Vp/128, ld_part] partial sums of E (z - ref) (entropy), kEntropy only
   float* z_target;                 // [ld_part] exact target logits
@@ -367,7 +536,6 @@ struct LogitsEpilogue {
     const int l32 = lane & 31, lhi = lane >> 5;
     const int granule = v0 / kGranule;
     const bool all_rows_valid = v0 + kGranule <= V;
-    const bool odd = lane & 1;
     constexpr float kLog2e = 1.44269504088896340736f, kLn2 = 0.69314718055994530942f;
 
     // exact target logit, if the target row lies in this granule and in this lane's half
@@ -389,14 +557,12 @@ struct LogitsEpilogue {
 
     // One pass over the accumulators, a 32 x 32 block at a time: E = exp(min(z - shift, 70)) as
     // 2^(min(z * log2(e) - shift * log2(e), 70 * log2(e))) (one fma, one min and the hardware exponential
-    // per logit, sixteen at a time with independent temporaries), its running sums, and at once both
-    // stores of the block, so that the stores of one block are in flight under the exponentials of the
-    // next:
-    //   Et (rows = vocabulary, k = token): neighbouring lanes hold neighbouring tokens; an exchange
-    //      with lane^1 lets even lanes store rows r (two tokens, 4 bytes) and odd lanes rows r+1;
-    //   Eb (rows = token, k = vocabulary): a lane holds 4 consecutive vocabulary entries of its token;
-    //      64 vocabulary rows at a time are staged through this wavefront's own part of the LDS ring
-    //      (free after the k-loop) and leave as 16-byte stores, 1 KiB contiguous per instruction.
+    // per logit, sixteen at a time with independent temporaries), its running sums, and at once the
+    // store of the block, so that the stores of one block are in flight under the exponentials of the
+    // next.  E is stored once, rows = token, k = vocabulary (the dH contraction reads it as it is, the
+    // dW contraction through the transposing LDS read): a lane holds 4 consecutive vocabulary entries
+    // of its token; 64 vocabulary rows at a time are staged through this wavefront's own part of the
+    // LDS ring (free after the k-loop) and leave as 16-byte stores, 1 KiB contiguous per instruction.
     // The staging area is private to the wavefront and LDS operations of one wavefront execute in
     // order, so no barrier is needed between its writes, its reads and the next half's writes.
     float s4[NB][4], t4[NB][4];
@@ -410,7 +576,6 @@ struct LogitsEpilogue {
 #pragma unroll
       for (int nb = 0; nb < NB; ++nb) {
         const float nshift2 = -pre.shift[nb] * kLog2e;
-        const int kk_pair = k0 + nb * 32 + (l32 & ~1);
 #pragma unroll
         for (int mbh = 0; mbh < 2; ++mbh) {
           const int mb = half * 2 + mbh;
@@ -436,15 +601,6 @@ struct LogitsEpilogue {
               w.x = pack_bf16x2(e[4 * r4], e[4 * r4 + 1]);
               w.y = pack_bf16x2(e[4 * r4 + 2], e[4 * r4 + 3]);
               *(uint2*)(stage + (nb * 32 + l32) * kStageRow + (mbh * 32 + 8 * r4 + 4 * lhi) * 2) = w;
-            }
-#pragma unroll
-            for (int r = 0; r < 16; r += 2) {
-              const float x = e[r], yv = e[r + 1];
-              const float give = odd ? x : yv;
-              const float got = __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, give), 0xB1, 0xF, 0xF, true));
-              const float lo = odd ? got : x, hi = odd ? yv : got;
-              const int v = v0 + mb * 32 + 8 * (r >> 2) + 4 * lhi + (r & 3) + (odd ? 1 : 0);
-              NAT_E_STORE((uint32_t*)(Et + blk_off(v, kk_pair, kb_e)), pack_bf16x2(lo, hi));
             }
           }
         }
@@ -675,18 +831,16 @@ logp_stats_kernel(const float* __restrict__ s_part, const float* __restrict__ t_
   }
 }
 
-// Overwrite the target entry of every valid token in both copies of E (see token_stats_kernel);
-// a token whose id lies outside [0, V) has no target entry.
+// Overwrite the target entry of every valid token in E (see token_stats_kernel); a token whose id
+// lies outside [0, V) has no target entry.
 __global__ void __launch_bounds__(256)
-patch_target_kernel(uint16_t* __restrict__ Et, int kb_e, uint16_t* __restrict__ Eb, int kb_z,
+patch_target_kernel(uint16_t* __restrict__ Eb, int kb_z,
                     const int32_t* __restrict__ ids, const float* __restrict__ patch, int n_valid, int V) {
   const int kk = blockIdx.x * blockDim.x + threadIdx.x;
   if (kk >= n_valid) return;
   const int y = ids[kk];
   if (y < 0 || y >= V) return;
-  const uint16_t bits = f32_to_bf16_bits(patch[kk]);
-  Et[blk_off(y, kk, kb_e)] = bits;
-  Eb[blk_off(kk, y, kb_z)] = bits;
+  Eb[blk_off(kk, y, kb_z)] = f32_to_bf16_bits(patch[kk]);
 }
 
 // -------------------------------------------------------------- host side ----
@@ -694,7 +848,7 @@ static inline int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * 
 
 struct Bf16Plan {
   int64_t Vp, Hp; int n_granules; int cap;      // padded vocabulary / hidden size, granules, chunk capacity (tokens)
-  size_t off_Wb, off_Wtb, off_Hb, off_Hktb, off_Et, off_Eb, off_s, off_t, off_zt, off_ref, off_beta, off_patch, off_term, total;
+  size_t off_Wb, off_Wtb, off_Hb, off_Hktb, off_Eb, off_s, off_t, off_zt, off_ref, off_beta, off_patch, off_term, total;
 };
 
 static Bf16Plan make_plan(int32_t N_k, int32_t H, int32_t V, int cap) {
@@ -709,8 +863,7 @@ static Bf16Plan make_plan(int32_t N_k, int32_t H, int32_t V, int cap) {
   p.off_Wtb = take((size_t)p.Hp * p.Vp * 2);    // W^T:  rows = hidden,     k = vocabulary
   p.off_Hb = take((size_t)cap * H * 2);         // H_chunk:   rows = tokens, k = hidden
   p.off_Hktb = take((size_t)p.Hp * cap * 2);    // H_chunk^T: rows = hidden, k = tokens
-  p.off_Et = take((size_t)p.Vp * cap * 2);      // E: rows = vocabulary, k = tokens
-  p.off_Eb = take((size_t)cap * p.Vp * 2);      // E: rows = tokens, k = vocabulary
+  p.off_Eb = take((size_t)cap * p.Vp * 2);      // E: rows = tokens, k = vocabulary (its one copy)
   p.off_s = take((size_t)p.n_granules * cap * 4);
   p.off_t = take((size_t)p.n_granules * cap * 4);
   p.off_zt = take((size_t)cap * 4);
@@ -755,10 +908,10 @@ size_t logp_bf16_workspace_bytes(int32_t N_k, int32_t H, int32_t V, bool minimal
   return make_fwd_plan(H, V, minimal ? kBN : recommended_cap(N_k)).total;
 }
 
-template <int NW, class Epi>
+template <int NW, class Epi, bool AT = false>
 static nat_status launch_gemm(const GemmArgs& g, const Epi& epi, int prof_class, hipStream_t s) {
   ProfScope prof(prof_class, s);
-  gemm_nt_kernel<Epi, NW><<<g.tiles_m * g.tiles_n, NW * 64, 0, s>>>(g, epi);
+  gemm_nt_kernel<Epi, NW, AT><<<g.tiles_m * g.tiles_n, NW * 64, 0, s>>>(g, epi);
   NAT_LAUNCH_CHECK();
   return NAT_OK;
 }
@@ -775,7 +928,6 @@ nat_status loss_bf16_run(const LossArgs& a) {
   uint16_t* Wtb = (uint16_t*)(ws + p.off_Wtb);
   uint16_t* Hb = (uint16_t*)(ws + p.off_Hb);
   uint16_t* Hktb = (uint16_t*)(ws + p.off_Hktb);
-  uint16_t* Et = (uint16_t*)(ws + p.off_Et);
   uint16_t* Eb = (uint16_t*)(ws + p.off_Eb);
   float* s_part = (float*)(ws + p.off_s);
   float* t_part = a.entropy_out ? (float*)(ws + p.off_t) : nullptr;
@@ -812,17 +964,16 @@ nat_status loss_bf16_run(const LossArgs& a) {
     for (int s0 = 0; s0 < nv; s0 += kSubChunk) {
       const int snv = nv - s0 < kSubChunk ? nv - s0 : kSubChunk;
       const int snp = (int)round_up(snv, kBN);
-      uint16_t* Et_s = Et + (int64_t)(s0 / 32) * kBlkElems;                 // k-slice s0 / 32 of every vocabulary tile
       uint16_t* Eb_s = Eb + (int64_t)(s0 / 256) * (Vp / 32) * kBlkElems;    // token tile s0 / 256
       const int32_t* ids_s = a.ids + c0 + s0;
       {  // logits: rows = vocabulary, columns = tokens, contraction over the hidden size
         GemmArgs g{Wb, Hb + (int64_t)(s0 / 256) * (H / 32) * kBlkElems, H, Vp / kBM, snp / kBN, NAT_GROUP_LOGITS};
         nat_status st;
         if (t_part) {
-          LogitsEpilogue<true> e{V, snv, cap, np / 32, Vp / 32, Et_s, Eb_s, s_part + s0, t_part + s0, zt + s0, ids_s, ref + s0};
+          LogitsEpilogue<true> e{V, snv, cap, Vp / 32, Eb_s, s_part + s0, t_part + s0, zt + s0, ids_s, ref + s0};
           st = launch_gemm<NAT_WAVES_LOGITS>(g, e, PC_LOGITS, s);
         } else {
-          LogitsEpilogue<false> e{V, snv, cap, np / 32, Vp / 32, Et_s, Eb_s, s_part + s0, nullptr, zt + s0, ids_s, ref + s0};
+          LogitsEpilogue<false> e{V, snv, cap, Vp / 32, Eb_s, s_part + s0, nullptr, zt + s0, ids_s, ref + s0};
           st = launch_gemm<NAT_WAVES_LOGITS>(g, e, PC_LOGITS, s);
         }
         if (st != NAT_OK) return st;
@@ -835,7 +986,7 @@ nat_status loss_bf16_run(const LossArgs& a) {
                                                           KlArgs{a.ref_logp, a.beta_kl, a.kl_kind}, beta + s0, patch + s0,
                                                           a.logp, a.kl_out, a.entropy_out, term, a.diag);
         NAT_LAUNCH_CHECK();
-        patch_target_kernel<<<(snv + 255) / 256, 256, 0, s>>>(Et_s, np / 32, Eb_s, Vp / 32, ids_s, patch + s0, snv, V);
+        patch_target_kernel<<<(snv + 255) / 256, 256, 0, s>>>(Eb_s, Vp / 32, ids_s, patch + s0, snv, V);
         NAT_LAUNCH_CHECK();
       }
       {  // (diag(beta) H)^T of the sub-chunk into its k-slices of the chunk's blocked operand
@@ -852,9 +1003,10 @@ nat_status loss_bf16_run(const LossArgs& a) {
       }
     }
     {  // dW: rows = vocabulary, columns = hidden units, contraction over the chunk's (padded) tokens
-      GemmArgs g{Et, Hktb, np, Vp / kBM, Hp / kBN, NAT_GROUP_DWEIGHT};
+      // A = E from its one copy (rows = token), i.e. stored along this contraction's k axis
+      GemmArgs g{Eb, Hktb, np, Vp / kBM, Hp / kBN, NAT_GROUP_DWEIGHT, Vp / 32};
       DWeightEpilogue e{V, H, (c0 > 0 || a.accumulate_dw) ? 1 : 0, a.dW};
-      nat_status st = launch_gemm<NAT_WAVES_DWEIGHT>(g, e, PC_DWEIGHT, s);
+      nat_status st = launch_gemm<NAT_WAVES_DWEIGHT, DWeightEpilogue, true>(g, e, PC_DWEIGHT, s);
       if (st != NAT_OK) return st;
     }
   }
@@ -901,10 +1053,10 @@ nat_status logp_bf16_run(const LogpArgs& a) {
       GemmArgs g{Wb, Hb, H, Vp / kBM, np / kBN, NAT_GROUP_LOGITS};
       nat_status st;
       if (t_part) {
-        LogitsEpilogue<true, false> e{V, nv, cap, 0, 0, nullptr, nullptr, s_part, t_part, zt, a.ids + c0, ref};
+        LogitsEpilogue<true, false> e{V, nv, cap, 0, nullptr, s_part, t_part, zt, a.ids + c0, ref};
         st = launch_gemm<NAT_WAVES_LOGITS>(g, e, PC_LOGITS, s);
       } else {
-        LogitsEpilogue<false, false> e{V, nv, cap, 0, 0, nullptr, nullptr, s_part, nullptr, zt, a.ids + c0, ref};
+        LogitsEpilogue<false, false> e{V, nv, cap, 0, nullptr, s_part, nullptr, zt, a.ids + c0, ref};
         st = launch_gemm<NAT_WAVES_LOGITS>(g, e, PC_LOGITS, s);
       }
       if (st != NAT_OK) return st;

@@ -77,6 +77,9 @@ def parse_args():
     ap.add_argument("--ceilings", action="store_true",
                     help="instead of the loss benchmark: the practical ceilings on this GPU (HBM copy, matrix cores "
                          "with operands in registers, the vendor GEMM on the three contraction shapes of --workload)")
+    ap.add_argument("--copy-probe-gib", type=int, default=0,
+                    help="launch the library's plain copy kernel once on this many GiB before the timed region: a kernel "
+                         "of known size next to the path's kernels in a counter run (scales FETCH_SIZE / WRITE_SIZE)")
     ap.add_argument("--chunk-tokens", type=int, default=0,
                     help="cap the loss call's workspace so that it works in chunks of at most this many kept tokens "
                          "(a multiple of 256; 0 = the library's recommended workspace)")
@@ -363,6 +366,13 @@ def main():
     for w in range(args.warmup):
         step(w)
     torch.cuda.synchronize()
+    if args.copy_probe_gib:
+        nbytes = args.copy_probe_gib << 30
+        src = torch.zeros(nbytes, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        nat.nat_probe_copy(dst, src, nbytes)
+        torch.cuda.synchronize()
+        del src, dst
     nat.profile_collect()
     nat.profile_enable(True)
     ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)

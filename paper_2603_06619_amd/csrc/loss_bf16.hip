@@ -77,7 +77,7 @@ constexpr int kMaxChunk = 32768;                  // token rows per chunk (recom
 #ifndef NAT_SUBCHUNK
 #define NAT_SUBCHUNK 8192
 #endif
-constexpr int kSubChunk = NAT_SUBCHUNK;           // token rows per launch of the logits and dH contractions
+constexpr int kSubChunk = NAT_SUBCHUNK;           // smallest token count per launch of the logits and dH contractions
 
 // two floats -> two bf16 in one 32-bit word (lo in bits 0..15): one packed conversion instruction
 __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
@@ -170,6 +170,20 @@ __device__ __forceinline__ void tile_of_block(const GemmArgs& g, int& tm, int& t
 // chunk index would fall on 4 bank groups, so the chunk is XOR-ed with bits 2..3 of the row.
 __device__ __forceinline__ int lds_chunk_off(int r, int c) { return r * (kBK * 2) + ((c ^ ((r >> 2) & 3)) << 4); }
 
+// Direct-to-LDS loads as inline assembly (two consecutive KiB: the second through the immediate
+// offset, which the hardware adds to both addresses).  Used by the kernel variant whose fragment
+// reads include the transposing LDS read: the compiler gives that read no memory operand and
+// therefore waits, before every such read, for ALL direct-to-LDS loads it knows to be outstanding
+// (vmcnt(0) inside the k-loop: measured 20-30 % slower).  Loads issued here are invisible to that
+// bookkeeping; the kernel orders them against the LDS reads itself (its own vmcnt waits and
+// barriers), exactly as the pipeline's design already requires.  m0 carries the LDS base; the
+// compiler keeps nothing in m0 across statements.
+__device__ __forceinline__ void dma_2kib(const uint16_t* gptr, const char* lds_dst) {
+  const uint32_t m0v = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(const __attribute__((address_space(3))) char*)lds_dst);
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off\n\tglobal_load_lds_dwordx4 %0, off offset:1024"
+               : : "v"(gptr), "s"(m0v) : "memory");
+}
+
 // Global -> LDS copy of one [256][32] bf16 operand block (16 KiB, contiguous in memory)
 // without staging registers: the NW wavefronts issue 16 direct-to-LDS loads of 16 bytes per
 // lane between them.  One instruction copies 1 KiB (16 tile rows) linearly: the hardware
@@ -185,6 +199,10 @@ struct TileLoader {
   // global and the LDS address, so one address and one LDS base serve all of them.
   __device__ __forceinline__ void init(const uint16_t* base, int tile, int kb, int wave, int lane) {
     src = base + (int64_t)tile * kb * kBlkElems + wave * (kLoads * 16 * kBK) + lane * 8;
+  }
+  // the same through dma_2kib (see there): 2 KiB per call, half = 0 .. kLoads / 2 - 1
+  __device__ __forceinline__ void issue_asm(char* lds_tile, int kt, int wave, int half) const {
+    dma_2kib(src + (int64_t)kt * kBlkElems + half * 1024, lds_tile + wave * (kLoads * 1024) + half * 2048);
   }
   __device__ __forceinline__ void issue(char* lds_tile, int kt, int wave) const {
     const uint16_t* p = src + (int64_t)kt * kBlkElems;
@@ -221,21 +239,13 @@ struct TileLoaderKMajor {
     tile_stride = (int64_t)kb_src * kBlkElems;
   }
   __device__ __forceinline__ void issue(char* lds_tile, int kt, int wave) const {
-    const uint16_t* p = src + (int64_t)(kt >> 3) * tile_stride + (kt & 7) * 1024;
-    char* dst = lds_tile + wave * (kPieces * 2048);
-    static_assert(kPieces == 2 || kPieces == 1, "written out below");
-    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)p,
-                                     (__attribute__((address_space(3))) void*)dst, 16, 0, 0);
-    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)p,
-                                     (__attribute__((address_space(3))) void*)dst, 16, 1024, 0);
-    if (kPieces == 2) {
-      const uint16_t* p2 = p + kBlkElems;
-      char* dst2 = dst + 2048;
-      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)p2,
-                                       (__attribute__((address_space(3))) void*)dst2, 16, 0, 0);
-      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)p2,
-                                       (__attribute__((address_space(3))) void*)dst2, 16, 1024, 0);
-    }
+#pragma unroll
+    for (int piece = 0; piece < kPieces; ++piece) issue_asm(lds_tile, kt, wave, piece);
+  }
+  // piece = 0 .. kPieces - 1 of this wavefront, 2 KiB each, through dma_2kib (see there)
+  __device__ __forceinline__ void issue_asm(char* lds_tile, int kt, int wave, int piece) const {
+    dma_2kib(src + (int64_t)(kt >> 3) * tile_stride + (kt & 7) * 1024 + (int64_t)piece * kBlkElems,
+             lds_tile + (wave * kPieces + piece) * 2048);
   }
 };
 
@@ -261,21 +271,33 @@ struct KMajorFragOffsets {
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef short s16x8 __attribute__((ext_vector_type(8)));
 
-// The transposing LDS read as inline assembly: through the compiler's builtin every such read is
-// preceded by a wait for ALL outstanding direct-to-LDS loads (it carries no memory operand, so the
-// wait-count pass assumes it may alias them), which serialises the k-loop's prefetch (measured: the
-// dW contraction 20-30 % slower).  The compiler does not know that this statement reads LDS: the code
-// that uses it waits for lgkmcnt itself before consuming the result, and orders it against the loads
-// with its own vmcnt waits and barriers, exactly as it does for the plain fragment reads.
-template <int kOffset>
-__device__ __forceinline__ s16x4 lds_read_tr16_b64(uint32_t lds_addr) {
-  s16x4 v;
-  asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(v) : "v"(lds_addr), "n"(kOffset));
-  return v;
+// fragments of k-substep ks with A in the k-major tile: four 32-row blocks from block a_blk0 (two
+// transposing reads each), NB blocks of B
+template <int NB>
+__device__ __forceinline__ void load_frags_kmajor(const char* a_s, const char* b_s, int a_blk0, int b_row0, int l32, int lhi,
+                                                  const KMajorFragOffsets& fo, int ks, bf16x8 (&af)[4], bf16x8 (&bfr)[NB]) {
+#pragma unroll
+  for (int j = 0; j < NB; ++j) bfr[j] = *(const bf16x8*)(b_s + lds_chunk_off(b_row0 + j * 32 + l32, ks * 2 + lhi));
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const char* piece = a_s + (a_blk0 + i) * 2048 + ks * 1024;
+    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(piece + fo.off[0]));
+    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(piece + fo.off[1]));
+    const s16x8 both = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+    af[i] = __builtin_bit_cast(bf16x8, both);
+  }
 }
 
-__device__ __forceinline__ uint32_t lds_addr_of(const char* p) {
-  return (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) char*)p;
+// Scheduling hints for M MFMAs with R LDS reads spread over them as evenly as the counts allow.
+template <int M, int R, int I = 0>
+__device__ __forceinline__ void interleave_reads() {
+  if constexpr (I < M) {
+    constexpr int per = R / M, extra = R % M;
+    constexpr int n_i = per + (I < extra ? 1 : 0);
+    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+    if constexpr (n_i > 0) __builtin_amdgcn_sched_group_barrier(0x100, n_i, 0);
+    interleave_reads<M, R, I + 1>();
+  }
 }
 
 // fragments of k-substep ks: four 32-row blocks of A from row a_row0, NB 32-row blocks of B from b_row0
@@ -340,81 +362,58 @@ gemm_nt_kernel(GemmArgs g, Epilogue epi) {
   lb.init(g.B, tn, kt_n, wave, lane);
 
   if constexpr (AT) {
-    // The pipeline described below, written out slot by slot: MFMA m of a k-substep is followed by the
-    // fragment reads (and, at the end of the second substep, the refill loads) given to its slot, and a
-    // scheduling fence keeps the compiler from regrouping them, since it cannot see what the assembly
-    // reads are.  A fragment of block i, substep ks = two transposing reads in piece a_blk0 + i at
-    // offset ks * 1024; B fragment j = one 16-byte read.
+    // The pipeline described below with the k-major A operand: fragments through the transposing read
+    // (two per fragment), refill loads through dma_2kib, 2 KiB per statement.  The compiler schedules the
+    // fragment reads among the MFMAs as hinted; the refill statements are placed by hand behind the last
+    // MFMAs of the second substep, one per MFMA.
+    constexpr int kDma = kLoadsPerWave / 2;                // refill statements per wavefront and slice (4 or 2)
+    constexpr int kReads = 8 + NB;                         // LDS reads per k-substep
     KMajorFragOffsets fo;
     fo.init(lane);
+    const int a_blk0 = a_row0 / 32;
+    auto refill = [&](int st, int k, int d) {              // statement d of the refill of stage st with slice k
+      if (d < kDma / 2) la.issue_asm(lds[st][0], k, wave, d);
+      else lb.issue_asm(lds[st][1], k, wave, d - kDma / 2);
+    };
 #pragma unroll
-    for (int st = 0; st < kStages; ++st) {
-      const int k = st < kt_n ? st : kt_n - 1;
-      la.issue(lds[st][0], k, wave);
-      lb.issue(lds[st][1], k, wave);
-    }
+    for (int st = 0; st < kStages; ++st)
+#pragma unroll
+      for (int d = 0; d < kDma; ++d) refill(st, st < kt_n ? st : kt_n - 1, d);
     __builtin_amdgcn_s_waitcnt(waitcnt_vm((kStages - 1) * kLoadsPerWave));
     __syncthreads();
-    s16x4 at[2][4][2];                                   // [substep][row block][q]
-    bf16x8 bt[2][NB];
-    const int a_blk0 = a_row0 / 32;
-    auto a_read = [&](const char* a_s, int ks, int i, int q) {
-      const uint32_t base = lds_addr_of(a_s) + fo.off[q] + a_blk0 * 2048;
-      switch (i * 2 + ks) {                              // the piece and the substep go into the immediate offset
-        case 0: at[ks][i][q] = lds_read_tr16_b64<0 * 2048 + 0>(base); break;
-        case 1: at[ks][i][q] = lds_read_tr16_b64<0 * 2048 + 1024>(base); break;
-        case 2: at[ks][i][q] = lds_read_tr16_b64<1 * 2048 + 0>(base); break;
-        case 3: at[ks][i][q] = lds_read_tr16_b64<1 * 2048 + 1024>(base); break;
-        case 4: at[ks][i][q] = lds_read_tr16_b64<2 * 2048 + 0>(base); break;
-        case 5: at[ks][i][q] = lds_read_tr16_b64<2 * 2048 + 1024>(base); break;
-        case 6: at[ks][i][q] = lds_read_tr16_b64<3 * 2048 + 0>(base); break;
-        default: at[ks][i][q] = lds_read_tr16_b64<3 * 2048 + 1024>(base); break;
-      }
-    };
-    auto a_frag = [&](int ks, int i) {
-      const s16x4 lo = at[ks][i][0], hi = at[ks][i][1];
-      const s16x8 both = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
-      return __builtin_bit_cast(bf16x8, both);
-    };
-    constexpr int kReads = 8 + NB;                       // per substep, in issue order: 8 for A, NB for B
-    auto read_slot = [&](const char* a_s, const char* b_s, int ks, int n) {
-      if (n < 8) a_read(a_s, ks, n >> 1, n & 1);
-      else bt[ks][n - 8] = *(const bf16x8*)(b_s + lds_chunk_off(b_row0 + (n - 8) * 32 + l32, ks * 2 + lhi));
-    };
-#pragma unroll
-    for (int n = 0; n < kReads; ++n) read_slot(lds[0][0], lds[0][1], 0, n);
+    bf16x8 af[2][4], bfr[2][NB];
+    load_frags_kmajor<NB>(lds[0][0], lds[0][1], a_blk0, b_row0, l32, lhi, fo, 0, af[0], bfr[0]);
 
     for (int kt = 0; kt < kt_n; ++kt) {
       const int cur = kt % kStages, nxt = (kt + 1) % kStages;
-      // first k-substep; under it the reads of the second one
-      __builtin_amdgcn_s_waitcnt(0xc07f);               // lgkmcnt(0): the fragments of substep 0 have landed
+      // first k-substep of slice kt; the second substep's fragments are read under its MFMAs
+      load_frags_kmajor<NB>(lds[cur][0], lds[cur][1], a_blk0, b_row0, l32, lhi, fo, 1, af[1], bfr[1]);
+      mfma_substep<NB>(acc, af[0], bfr[0]);
+      interleave_reads<kMfma, kReads>();
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < NB; ++j) asm volatile("" : "+a"(acc[i][j]));
       __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-      for (int m = 0; m < kMfma; ++m) {
-        const int i = m / NB, j = m % NB;
-        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_frag(0, i), bt[0][j], acc[i][j], 0, 0, 0);
-#pragma unroll
-        for (int n = m * kReads / kMfma; n < (m + 1) * kReads / kMfma; ++n) read_slot(lds[cur][0], lds[cur][1], 1, n);
-        __builtin_amdgcn_sched_barrier(0);
-      }
-      // slice kt+1 has landed (this wavefront's share; the barrier covers the others) and this wavefront's
-      // reads of slice kt have returned, so its buffer can be refilled below
+      // slice kt+1 has landed (this wavefront's share; the barrier covers the others) and this wavefront
+      // has finished reading slice kt, whose buffer is refilled below
       __builtin_amdgcn_s_waitcnt(waitcnt_vm((kStages - 2) * kLoadsPerWave) & 0xf0ff);
       __builtin_amdgcn_s_barrier();
       __builtin_amdgcn_sched_barrier(0);
-      // second k-substep; under it the first reads of slice kt+1, then the refill of lds[cur]
+      // second k-substep; under it the first fragments of slice kt+1, then the refill of lds[cur]
+      load_frags_kmajor<NB>(lds[nxt][0], lds[nxt][1], a_blk0, b_row0, l32, lhi, fo, 0, af[0], bfr[0]);
       int k2 = kt + kStages;
       k2 = k2 < kt_n ? k2 : kt_n - 1;
-      constexpr int kFirst = kMfma - 2;                  // the last two slots issue the refill
+      constexpr int kHead = kMfma - kDma;                  // MFMAs that carry the fragment reads
 #pragma unroll
-      for (int m = 0; m < kMfma; ++m) {
-        const int i = m / NB, j = m % NB;
-        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_frag(1, i), bt[1][j], acc[i][j], 0, 0, 0);
+      for (int m = 0; m < kHead; ++m)
+        acc[m / NB][m % NB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[1][m / NB], bfr[1][m % NB], acc[m / NB][m % NB], 0, 0, 0);
+      interleave_reads<kHead, kReads>();
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int n = m * kReads / kFirst; n < (m + 1) * kReads / kFirst && m < kFirst; ++n)
-          read_slot(lds[nxt][0], lds[nxt][1], 0, n);
-        if (m == kMfma - 2) la.issue(lds[cur][0], k2, wave);
-        if (m == kMfma - 1) lb.issue(lds[cur][1], k2, wave);
+      for (int m = kHead; m < kMfma; ++m) {
+        acc[m / NB][m % NB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[1][m / NB], bfr[1][m % NB], acc[m / NB][m % NB], 0, 0, 0);
+        refill(cur, k2, m - kHead);
         __builtin_amdgcn_sched_barrier(0);
       }
     }
@@ -875,6 +874,22 @@ static Bf16Plan make_plan(int32_t N_k, int32_t H, int32_t V, int cap) {
   return p;
 }
 
+// Token rows per launch of the logits and dH contractions inside a chunk of `cap` rows: the smallest
+// multiple of kSubChunk whose dH launch (rows / 256 x Hp / 256 tiles) fills whole waves of kNumCU
+// workgroups to at least 97 %; the whole chunk if none does.  (Hp = 4096: 8192 rows = 512 tiles;
+// Hp = 5120: 16384 rows = 1280 tiles; Hp = 3584 and 1024: the whole chunk.)
+constexpr int kNumCU = 256;
+static int sub_chunk_rows(int cap, int Hp) {
+  if (kSubChunk < 8192) return kSubChunk < cap ? kSubChunk : cap;   // a test build: the sub-chunk logic on small shapes
+  const int n_col = Hp / kBN;
+  for (int rows = kSubChunk; rows < cap; rows += kSubChunk) {
+    const int tiles = rows / kBM * n_col;
+    const int waves = (tiles + kNumCU - 1) / kNumCU;
+    if (tiles * 100 >= waves * kNumCU * 97) return rows;
+  }
+  return cap;
+}
+
 static int recommended_cap(int32_t N_k) {
   int64_t cap = round_up(N_k > 0 ? N_k : 1, kBN);
   return (int)(cap > kMaxChunk ? kMaxChunk : cap);
@@ -946,6 +961,7 @@ nat_status loss_bf16_run(const LossArgs& a) {
     pack_blocked_kernel<<<dim3(Vp / 64, Hp / 64), 256, 0, s>>>(W, H, V, H, Vp, Hp, Wb, Wtb, Vp / 32, nullptr);
     NAT_LAUNCH_CHECK();
   }
+  const int sub = sub_chunk_rows(cap, Hp);
   for (int c0 = 0; c0 < a.N_k; c0 += cap) {
     const int nv = a.N_k - c0 < cap ? a.N_k - c0 : cap;
     const int np = (int)round_up(nv, kBN);
@@ -961,8 +977,8 @@ nat_status loss_bf16_run(const LossArgs& a) {
     // the three contractions alternate, which this power-limited part rewards with a higher clock
     // (measured: both run faster on 8192 tokens than on 32768), while the dW contraction below keeps
     // the whole chunk as its contraction axis (it is the one that loses on short axes).
-    for (int s0 = 0; s0 < nv; s0 += kSubChunk) {
-      const int snv = nv - s0 < kSubChunk ? nv - s0 : kSubChunk;
+    for (int s0 = 0; s0 < nv; s0 += sub) {
+      const int snv = nv - s0 < sub ? nv - s0 : sub;
       const int snp = (int)round_up(snv, kBN);
       uint16_t* Eb_s = Eb + (int64_t)(s0 / 256) * (Vp / 32) * kBlkElems;    // token tile s0 / 256
       const int32_t* ids_s = a.ids + c0 + s0;

@@ -513,7 +513,7 @@ struct LogitsEpilogue {
   const int32_t* ids;              // target ids of the chunk's tokens
   const float* ref;                // [ld_part] exponent shift per token
 
-  static constexpr int kStageRow = 144;        // bytes per token row of the LDS staging tile (64 bf16 + pad)
+  static constexpr int kStageRow = 272;        // bytes per token row of the LDS staging tile (128 bf16 + pad)
 
   template <int NB> struct Pre { int y[NB]; float shift[NB]; };
   template <int NB>
@@ -554,74 +554,63 @@ struct LogitsEpilogue {
       }
     }
 
-    // One pass over the accumulators, a 32 x 32 block at a time: E = exp(min(z - shift, 70)) as
-    // 2^(min(z * log2(e) - shift * log2(e), 70 * log2(e))) (one fma, one min and the hardware exponential
-    // per logit, sixteen at a time with independent temporaries), its running sums, and at once the
-    // store of the block, so that the stores of one block are in flight under the exponentials of the
-    // next.  E is stored once, rows = token, k = vocabulary (the dH contraction reads it as it is, the
-    // dW contraction through the transposing LDS read): a lane holds 4 consecutive vocabulary entries
-    // of its token; 64 vocabulary rows at a time are staged through this wavefront's own part of the
-    // LDS ring (free after the k-loop) and leave as 16-byte stores, 1 KiB contiguous per instruction.
-    // The staging area is private to the wavefront and LDS operations of one wavefront execute in
-    // order, so no barrier is needed between its writes, its reads and the next half's writes.
-    float s4[NB][4], t4[NB][4];
+    // One pass over the accumulators, 32 token columns (all 128 vocabulary rows of the wavefront) at a
+    // time: E = exp(min(z - shift, 70)) as 2^(min(z * log2(e) - shift * log2(e), 70 * log2(e))) (one fma,
+    // one min and the hardware exponential per logit, sixteen at a time with independent temporaries),
+    // its running sums, and at once the store of those columns, so that the stores of one group are in
+    // flight under the exponentials of the next.  E is stored once, rows = token, k = vocabulary (the
+    // dH contraction reads it as it is, the dW contraction through the transposing LDS read): a lane
+    // holds 4 consecutive vocabulary entries of its token; the 32 x 128 group is staged through this
+    // wavefront's own part of the LDS ring (free after the k-loop) and leaves as 16-byte stores, 1 KiB
+    // (16 token rows of one 32-wide vocabulary slice) contiguous per instruction.  The staging area is
+    // private to the wavefront and LDS operations of one wavefront execute in order, so no barrier is
+    // needed between its writes, its reads and the next group's writes.
+    char* stage = lds + wave * (32 * kStageRow);
 #pragma unroll
-    for (int nb = 0; nb < NB; ++nb)
+    for (int nb = 0; nb < NB; ++nb) {
+      const float nshift2 = -pre.shift[nb] * kLog2e;
+      float s2[2] = {0.f, 0.f}, t2[2] = {0.f, 0.f};        // two independent chains per sum
 #pragma unroll
-      for (int q = 0; q < 4; ++q) { s4[nb][q] = 0.f; t4[nb][q] = 0.f; }
-    char* stage = lds + wave * (kTok * kStageRow);
+      for (int mb = 0; mb < 4; ++mb) {
+        float x2[16], e[16];
 #pragma unroll
-    for (int half = 0; half < 2; ++half) {
+        for (int r = 0; r < 16; ++r) x2[r] = fminf(fmaf(acc[mb][nb][r], kLog2e, nshift2), 70.f * kLog2e);
 #pragma unroll
-      for (int nb = 0; nb < NB; ++nb) {
-        const float nshift2 = -pre.shift[nb] * kLog2e;
+        for (int r = 0; r < 16; ++r) e[r] = __builtin_amdgcn_exp2f(x2[r]);
+        if (!all_rows_valid) {                             // only the last vocabulary tile pays for the row check
 #pragma unroll
-        for (int mbh = 0; mbh < 2; ++mbh) {
-          const int mb = half * 2 + mbh;
-          float x2[16], e[16];
+          for (int r = 0; r < 16; ++r)
+            if (v0 + mb * 32 + 8 * (r >> 2) + 4 * lhi + (r & 3) >= V) e[r] = 0.f;
+        }
 #pragma unroll
-          for (int r = 0; r < 16; ++r) x2[r] = fminf(fmaf(acc[mb][nb][r], kLog2e, nshift2), 70.f * kLog2e);
+        for (int r = 0; r < 16; ++r) {
+          s2[r & 1] += e[r];
+          if (kEntropy) t2[r & 1] = fmaf(e[r], x2[r], t2[r & 1]);
+        }
+        if (kStoreE) {
 #pragma unroll
-          for (int r = 0; r < 16; ++r) e[r] = __builtin_amdgcn_exp2f(x2[r]);
-          if (!all_rows_valid) {                           // only the last vocabulary tile pays for the row check
-#pragma unroll
-            for (int r = 0; r < 16; ++r)
-              if (v0 + mb * 32 + 8 * (r >> 2) + 4 * lhi + (r & 3) >= V) e[r] = 0.f;
-          }
-#pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            s4[nb][r & 3] += e[r];
-            if (kEntropy) t4[nb][r & 3] = fmaf(e[r], x2[r], t4[nb][r & 3]);
-          }
-          if (kStoreE) {
-#pragma unroll
-            for (int r4 = 0; r4 < 4; ++r4) {
-              uint2 w;
-              w.x = pack_bf16x2(e[4 * r4], e[4 * r4 + 1]);
-              w.y = pack_bf16x2(e[4 * r4 + 2], e[4 * r4 + 3]);
-              *(uint2*)(stage + (nb * 32 + l32) * kStageRow + (mbh * 32 + 8 * r4 + 4 * lhi) * 2) = w;
-            }
+          for (int r4 = 0; r4 < 4; ++r4) {
+            uint2 w;
+            w.x = pack_bf16x2(e[4 * r4], e[4 * r4 + 1]);
+            w.y = pack_bf16x2(e[4 * r4 + 2], e[4 * r4 + 3]);
+            *(uint2*)(stage + l32 * kStageRow + (mb * 32 + 8 * r4 + 4 * lhi) * 2) = w;
           }
         }
       }
       if (kStoreE) {
 #pragma unroll
-        for (int i = 0; i < kTok / 8; ++i) {
-          const int q = i * 64 + lane;                    // slice q/(4 kTok), token (q%(4 kTok))/4, 16-byte chunk q%4
-          const int sl = q / (4 * kTok), tok = (q % (4 * kTok)) >> 2, ch = q & 3;
+        for (int i = 0; i < 8; ++i) {                      // vocabulary slice i / 2, token rows (i % 2) * 16 .. + 15
+          const int sl = i >> 1, tok = (i & 1) * 16 + (lane >> 2), ch = lane & 3;
           const uint4 val = *(const uint4*)(stage + tok * kStageRow + sl * 64 + ch * 16);
-          NAT_E_STORE((u32x4v*)(Eb + blk_off(k0 + tok, v0 + half * 64 + sl * 32 + ch * 8, kb_z)), __builtin_bit_cast(u32x4v, val));
+          NAT_E_STORE((u32x4v*)(Eb + blk_off(k0 + nb * 32 + tok, v0 + sl * 32 + ch * 8, kb_z)), __builtin_bit_cast(u32x4v, val));
         }
       }
-    }
-#pragma unroll
-    for (int nb = 0; nb < NB; ++nb) {
       const int kk = k0 + nb * 32 + l32;                   // token column (always inside the padded chunk)
-      float s = (s4[nb][0] + s4[nb][1]) + (s4[nb][2] + s4[nb][3]);
-      s += __shfl_xor(s, 32);
-      if (lhi == 0) s_part[(int64_t)granule * ld_part + kk] = s;
+      float sum = s2[0] + s2[1];
+      sum += __shfl_xor(sum, 32);
+      if (lhi == 0) s_part[(int64_t)granule * ld_part + kk] = sum;
       if (kEntropy) {
-        float t = ((t4[nb][0] + t4[nb][1]) + (t4[nb][2] + t4[nb][3])) * kLn2;     // back to natural-log units
+        float t = (t2[0] + t2[1]) * kLn2;                  // back to natural-log units
         t += __shfl_xor(t, 32);
         if (lhi == 0) t_part[(int64_t)granule * ld_part + kk] = t;
       }

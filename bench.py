@@ -23,13 +23,13 @@ GEMM_CLASSES = ("logits_gemm", "dhidden_gemm", "dweight_gemm")
 # L2-miss traffic per launch (bytes, average over the launches of one default step) from two
 # rocprofv3 --pmc runs of this file (FETCH_SIZE, then WRITE_SIZE, KiB per dispatch), each scaled by
 # what the same counter reads for the library's row-gather copy kernel of known size
-# (factors 1.954 and 0.993; see profiles/).  Valid only for the kernel source they were taken
+# (factors 2.000 and 1.000; see profiles/).  Valid only for the kernel source they were taken
 # on: bench.py reports null when the source hash differs.
-TRAFFIC_SOURCE_SHA256_16 = "45705dc67a28f7a3"
+TRAFFIC_SOURCE_SHA256_16 = "355c0ab0c6e2176f"
 TRAFFIC_BYTES_PER_LAUNCH = {
-    "logits_gemm": 65543609370 + 17900139593,
-    "dhidden_gemm": 58327438404 + 232602473,
-    "dweight_gemm": 63550641197 + 2607756566,
+    "logits_gemm": 16349029090 + 2455971236,
+    "dhidden_gemm": 14703526987 + 65053127,
+    "dweight_gemm": 88253179113 + 2664497152,
 }
 
 

@@ -74,6 +74,7 @@ constexpr int kTileBytes = kBM * kBK * 2;         // 16 KiB per operand per stag
 #define NAT_WAVES_DWEIGHT 8
 #endif
 constexpr int kMaxChunk = 32768;                  // token rows per chunk (recommended workspace)
+constexpr int kNumCU = 256;                       // compute units (one workgroup of these kernels each)
 #ifndef NAT_SUBCHUNK
 #define NAT_SUBCHUNK 8192
 #endif
@@ -144,14 +145,15 @@ struct GemmArgs {
   int tiles_m, tiles_n;
   int group_m;                // tile rows walked together (see tile_of_block)
   int kb_a_src;               // k-major A only (see TileLoaderKMajor): k-slices of the source operand
+  int k_splits;               // > 1: the contraction axis is cut into this many ranges of kt_per_split k-slices, one
+  int kt_per_split;           // workgroup per (tile, range); the epilogue is told its range (row-major operands only)
 };
 
 // Block id -> output tile.  Blocks are dealt round-robin to the 8 XCDs, so ids
 // congruent mod 8 share an L2: give each XCD a contiguous range of tiles, walked
 // in groups of `group_m` tile-rows so that concurrently resident blocks reuse A and B tiles.
-__device__ __forceinline__ void tile_of_block(const GemmArgs& g, int& tm, int& tn) {
+__device__ __forceinline__ void tile_of_block(const GemmArgs& g, int pid, int& tm, int& tn) {
   const int total = g.tiles_m * g.tiles_n;
-  const int pid = blockIdx.x;
   int logical = pid;
   const int per_xcd = total / 8;
   if (pid < per_xcd * 8) logical = (pid & 7) * per_xcd + (pid >> 3);
@@ -200,6 +202,7 @@ struct TileLoader {
   __device__ __forceinline__ void init(const uint16_t* base, int tile, int kb, int wave, int lane) {
     src = base + (int64_t)tile * kb * kBlkElems + wave * (kLoads * 16 * kBK) + lane * 8;
   }
+  __device__ __forceinline__ void start_at(int kt0) { src += (int64_t)kt0 * kBlkElems; }   // slice 0 := slice kt0
   // the same through dma_2kib (see there): 2 KiB per call, half = 0 .. kLoads / 2 - 1
   __device__ __forceinline__ void issue_asm(char* lds_tile, int kt, int wave, int half) const {
     dma_2kib(src + (int64_t)kt * kBlkElems + half * 1024, lds_tile + wave * (kLoads * 1024) + half * 2048);
@@ -335,7 +338,9 @@ gemm_nt_kernel(GemmArgs g, Epilogue epi) {
   constexpr int kMfma = 4 * NB, kFragReads = 4 + NB;           // per k-substep
   __shared__ __attribute__((aligned(1024))) char lds[kStages][2][kTileBytes];
   int tm, tn;
-  tile_of_block(g, tm, tn);
+  const int n_tiles = g.tiles_m * g.tiles_n;
+  const int split = g.k_splits > 1 ? (int)blockIdx.x / n_tiles : 0;
+  tile_of_block(g, (int)blockIdx.x - split * n_tiles, tm, tn);
   const int m0 = tm * kBM, n0 = tn * kBN;
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -357,9 +362,18 @@ gemm_nt_kernel(GemmArgs g, Epilogue epi) {
 
   typename std::conditional<AT, TileLoaderKMajor<NW>, TileLoader<NW>>::type la;
   TileLoader<NW> lb;
-  const int kt_n = g.K / kBK;
-  la.init(g.A, tm, AT ? g.kb_a_src : kt_n, wave, lane);
-  lb.init(g.B, tn, kt_n, wave, lane);
+  const int kt_all = g.K / kBK;
+  la.init(g.A, tm, AT ? g.kb_a_src : kt_all, wave, lane);
+  lb.init(g.B, tn, kt_all, wave, lane);
+  int kt_n = kt_all;                                           // k-slices this workgroup contracts over
+  if constexpr (!AT) {
+    if (g.k_splits > 1) {
+      const int kt0 = split * g.kt_per_split;
+      kt_n = kt_all - kt0 < g.kt_per_split ? kt_all - kt0 : g.kt_per_split;
+      la.start_at(kt0);
+      lb.start_at(kt0);
+    }
+  }
 
   if constexpr (AT) {
     // The pipeline described below with the k-major A operand: fragments through the transposing read
@@ -419,7 +433,7 @@ gemm_nt_kernel(GemmArgs g, Epilogue epi) {
     }
     __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));   // no direct-to-LDS load may outlive the block
     __syncthreads();
-    epi(acc, pre, m0 + a_row0, n0 + b_row0, lane, wave, &lds[0][0][0]);
+    epi(acc, pre, m0 + a_row0, n0 + b_row0, lane, wave, &lds[0][0][0], split);
     return;
   }
 
@@ -495,7 +509,7 @@ gemm_nt_kernel(GemmArgs g, Epilogue epi) {
   __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));   // no direct-to-LDS load may outlive the block
   __syncthreads();
 
-  epi(acc, pre, m0 + a_row0, n0 + b_row0, lane, wave, &lds[0][0][0]);
+  epi(acc, pre, m0 + a_row0, n0 + b_row0, lane, wave, &lds[0][0][0], split);
 }
 
 // ------------------------------------------------------------- epilogues ----
@@ -530,7 +544,7 @@ struct LogitsEpilogue {
 
   template <int NB>
   __device__ __forceinline__ void operator()(f32x16 (&acc)[4][NB], const Pre<NB>& pre, int v0, int k0, int lane, int wave,
-                                             char* lds) const {
+                                             char* lds, int) const {
     constexpr int kTok = NB * 32;                          // token columns of this wavefront
     const int l32 = lane & 31, lhi = lane >> 5;
     const int granule = v0 / kGranule;
@@ -623,13 +637,27 @@ struct DHiddenEpilogue {
   int n_valid, H;
   uint16_t* dH;                    // rows of this chunk, [n_valid, H] bf16
   const float* beta;               // [n_valid]
+  float* partial;                  // split contraction: [k_splits][rows_p][cols_p] fp32 partial sums (else NULL)
+  int rows_p, cols_p;              // padded token rows / hidden columns of the launch
 
   template <int NB> struct Pre {};
   template <int NB> __device__ __forceinline__ void prefetch(Pre<NB>&, int, int) const {}
   template <int NB>
   __device__ __forceinline__ void operator()(f32x16 (&acc)[4][NB], const Pre<NB>&, int k0, int h0, int lane, int,
-                                             char*) const {
+                                             char*, int split) const {
     const int l32 = lane & 31, lhi = lane >> 5;
+    if (partial) {                 // this workgroup's range of the vocabulary: the raw sums go to its slab
+      float* slab = partial + (int64_t)split * rows_p * cols_p;
+#pragma unroll
+      for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int k = k0 + mb * 32 + 8 * (r >> 2) + 4 * lhi + (r & 3);
+#pragma unroll
+          for (int nb = 0; nb < NB; ++nb) slab[(int64_t)k * cols_p + h0 + nb * 32 + l32] = acc[mb][nb][r];
+        }
+      return;
+    }
 #pragma unroll
     for (int mb = 0; mb < 4; ++mb)
 #pragma unroll
@@ -655,7 +683,7 @@ struct DWeightEpilogue {
   template <int NB> __device__ __forceinline__ void prefetch(Pre<NB>&, int, int) const {}
   template <int NB>
   __device__ __forceinline__ void operator()(f32x16 (&acc)[4][NB], const Pre<NB>&, int v0, int h0, int lane, int,
-                                             char*) const {
+                                             char*, int) const {
     const int l32 = lane & 31, lhi = lane >> 5;
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) {
@@ -674,6 +702,19 @@ struct DWeightEpilogue {
     }
   }
 };
+
+// dH of a launch whose contraction was split: dH[k][h] = beta_k * (slab 0 + slab 1 + ...), in slab order.
+__global__ void __launch_bounds__(256)
+dh_reduce_kernel(const float* __restrict__ partial, int k_splits, int rows_p, int cols_p, const float* __restrict__ beta,
+                 int n_valid, int H, uint16_t* __restrict__ dH) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  const int k = (int)(i / H), h = (int)(i % H);
+  if (k >= n_valid) return;
+  const int64_t slab = (int64_t)rows_p * cols_p;
+  float s = 0.f;
+  for (int sp = 0; sp < k_splits; ++sp) s += partial[sp * slab + (int64_t)k * cols_p + h];
+  dH[(int64_t)k * H + h] = f32_to_bf16_bits(beta[k] * s);
+}
 
 // ----------------------------------------------------- reference logit ----
 // ref[kk] = h_k . W[ids_k] in fp32, one wavefront per token (row-major caller arrays).
@@ -836,7 +877,7 @@ static inline int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * 
 
 struct Bf16Plan {
   int64_t Vp, Hp; int n_granules; int cap;      // padded vocabulary / hidden size, granules, chunk capacity (tokens)
-  size_t off_Wb, off_Wtb, off_Hb, off_Hktb, off_Eb, off_s, off_t, off_zt, off_ref, off_beta, off_patch, off_term, total;
+  size_t off_Wb, off_Wtb, off_Hb, off_Hktb, off_Eb, off_s, off_t, off_zt, off_ref, off_beta, off_patch, off_term, off_dh_part, total;
 };
 
 static Bf16Plan make_plan(int32_t N_k, int32_t H, int32_t V, int cap) {
@@ -859,6 +900,7 @@ static Bf16Plan make_plan(int32_t N_k, int32_t H, int32_t V, int cap) {
   p.off_beta = take((size_t)cap * 4);
   p.off_patch = take((size_t)cap * 4);
   p.off_term = take((size_t)(N_k > 0 ? N_k : 1) * 4);
+  p.off_dh_part = take((size_t)kNumCU * kBM * kBN * 4);   // partial dH tiles of a split contraction (see dh_splits): 64 MiB
   p.total = off;
   return p;
 }
@@ -867,7 +909,6 @@ static Bf16Plan make_plan(int32_t N_k, int32_t H, int32_t V, int cap) {
 // multiple of kSubChunk whose dH launch (rows / 256 x Hp / 256 tiles) fills whole waves of kNumCU
 // workgroups to at least 97 %; the whole chunk if none does.  (Hp = 4096: 8192 rows = 512 tiles;
 // Hp = 5120: 16384 rows = 1280 tiles; Hp = 3584 and 1024: the whole chunk.)
-constexpr int kNumCU = 256;
 static int sub_chunk_rows(int cap, int Hp) {
   if (kSubChunk < 8192) return kSubChunk < cap ? kSubChunk : cap;   // a test build: the sub-chunk logic on small shapes
   const int n_col = Hp / kBN;
@@ -940,6 +981,7 @@ nat_status loss_bf16_run(const LossArgs& a) {
   float* beta = (float*)(ws + p.off_beta);
   float* patch = (float*)(ws + p.off_patch);
   float* term = (float*)(ws + p.off_term);
+  float* dh_part = (float*)(ws + p.off_dh_part);
   const uint16_t* W = (const uint16_t*)a.W;
   const uint16_t* hidden = (const uint16_t*)a.hidden;
   const int H = a.H, V = a.V;
@@ -1001,10 +1043,26 @@ nat_status loss_bf16_run(const LossArgs& a) {
         NAT_LAUNCH_CHECK();
       }
       {  // dH: rows = tokens, columns = hidden units, contraction over the padded vocabulary
-        GemmArgs g{Eb_s, Wtb, Vp, snp / kBM, Hp / kBN, NAT_GROUP_DHIDDEN};
-        DHiddenEpilogue e{snv, H, (uint16_t*)a.dH + (int64_t)(c0 + s0) * H, beta + s0};
-        nat_status st = launch_gemm<NAT_WAVES_DHIDDEN>(g, e, PC_DHIDDEN, s);
-        if (st != NAT_OK) return st;
+        // a launch with fewer tiles than compute units cuts the vocabulary into ranges (one workgroup per tile
+        // and range, raw partial sums in fp32) and adds them up in range order afterwards
+        const int tiles = (snp / kBM) * (Hp / kBN);
+        int splits = tiles * 2 <= kNumCU ? kNumCU / tiles : 1;
+        if (splits > 8) splits = 8;
+        while (splits > 1 && (Vp / kBK) / splits < 64) --splits;
+        const int kt_per = (Vp / kBK + splits - 1) / splits;
+        uint16_t* dH_s = (uint16_t*)a.dH + (int64_t)(c0 + s0) * H;
+        GemmArgs g{Eb_s, Wtb, Vp, snp / kBM, Hp / kBN, NAT_GROUP_DHIDDEN, 0, splits, kt_per};
+        DHiddenEpilogue e{snv, H, dH_s, beta + s0, splits > 1 ? dh_part : nullptr, snp, Hp};
+        {
+          ProfScope prof(PC_DHIDDEN, s);
+          gemm_nt_kernel<DHiddenEpilogue, NAT_WAVES_DHIDDEN, false><<<tiles * splits, NAT_WAVES_DHIDDEN * 64, 0, s>>>(g, e);
+          NAT_LAUNCH_CHECK();
+          if (splits > 1) {
+            const int64_t n = (int64_t)snv * H;
+            dh_reduce_kernel<<<(unsigned)((n + 255) / 256), 256, 0, s>>>(dh_part, splits, snp, Hp, beta + s0, snv, H, dH_s);
+            NAT_LAUNCH_CHECK();
+          }
+        }
       }
     }
     {  // dW: rows = vocabulary, columns = hidden units, contraction over the chunk's (padded) tokens

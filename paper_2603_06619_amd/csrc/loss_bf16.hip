@@ -113,27 +113,44 @@ __host__ __device__ __forceinline__ int64_t blk_off(int row, int k, int kb) {
 //   kb_cr: k-slices of the operand out_cr belongs to (Rp / 32 when the input is the whole operand;
 //          more when the rows are a range of a longer contraction axis: out_cr then points at the
 //          range's first k-slice).
+// One workgroup repacks a 64 x 64 tile, 16 bytes (8 elements) per access on the global side: rows of
+// the input and 16-byte chunks of the blocked layout are both 16-byte aligned (C and ld_in multiples
+// of 8, pointers 16-byte aligned: checked at the entry points).
 __global__ void __launch_bounds__(256)
 pack_blocked_kernel(const uint16_t* __restrict__ in, int64_t ld_in, int R, int C, int Rp, int Cp,
                     uint16_t* __restrict__ out_rk, uint16_t* __restrict__ out_cr, int kb_cr,
                     const float* __restrict__ row_scale) {
-  __shared__ uint16_t tile[64][66];
+  union Chunk { uint4 q; uint16_t e[8]; };
+  __shared__ __attribute__((aligned(16))) uint16_t tile[64][72];     // 144-byte rows: 16-byte aligned chunks
   const int r0 = blockIdx.x * 64, c0 = blockIdx.y * 64;
-  const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
-  for (int j = ty; j < 64; j += 4) {
-    const int r = r0 + j, c = c0 + tx;
-    const uint16_t x = (r < R && c < C) ? in[(int64_t)r * ld_in + c] : (uint16_t)0;
-    if (out_rk && c < C) out_rk[blk_off(r, c, C >> 5)] = x;
-    if (row_scale && r < R)
-      tile[j][tx] = f32_to_bf16_bits(__builtin_bit_cast(float, (uint32_t)x << 16) * row_scale[r]);
-    else
-      tile[j][tx] = x;
+  const int cc = threadIdx.x & 7, jr = threadIdx.x >> 3;
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int j = jr + 32 * i;
+    const int r = r0 + j, c = c0 + 8 * cc;
+    Chunk x;
+    x.q = make_uint4(0u, 0u, 0u, 0u);
+    if (r < R && c < C) x.q = *reinterpret_cast<const uint4*>(in + (int64_t)r * ld_in + c);
+    if (out_rk && c < C) *reinterpret_cast<uint4*>(out_rk + blk_off(r, c, C >> 5)) = x.q;
+    if (row_scale && r < R) {
+      const float f = row_scale[r];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) x.e[e] = f32_to_bf16_bits(__builtin_bit_cast(float, (uint32_t)x.e[e] << 16) * f);
+    }
+    *reinterpret_cast<uint4*>(&tile[j][8 * cc]) = x.q;
   }
   if (!out_cr) return;
   __syncthreads();
-  for (int j = ty; j < 64; j += 4) {
-    const int c = c0 + j, r = r0 + tx;
-    out_cr[blk_off(c, r, kb_cr)] = tile[tx][j];
+  // transposed: row c of the output holds k = r; the tile's 64 r are two k-slices, each a contiguous
+  // 4 KiB (64 rows x 64 bytes) of the blocked operand; four neighbouring threads write one 64-byte row
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int q = threadIdx.x + 256 * i;
+    const int cj = (q >> 2) & 63, rbase = (q >> 8) * 32 + (q & 3) * 8;
+    Chunk y;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) y.e[e] = tile[rbase + e][cj];
+    *reinterpret_cast<uint4*>(out_cr + blk_off(c0 + cj, r0 + rbase, kb_cr)) = y.q;
   }
 }
 
@@ -751,33 +768,41 @@ target_logit_kernel(const uint16_t* __restrict__ hidden, const uint16_t* __restr
 // clamp of the exponent shift acts (a clamped numerator alone makes its granule's sum that large).
 constexpr float kShiftRangeLimit = 2.5154386709191669e30f;     // e^70
 
-// Per-token sums of the per-granule partials: 64 tokens per workgroup; the granules of a token are
-// split over 4 wavefronts (granule gi goes to wavefront gi % 4) and the four partial sums are added
-// in wavefront order, so the result does not depend on timing.  Returns to wavefront 0 only.
+// Per-token sums of the per-granule partials: kStatTokens tokens per workgroup; the granules of a
+// token are split over kStatParts groups of threads (granule gi goes to group gi % kStatParts), each
+// of which walks its granules in order, and the groups' sums are added in a fixed tree, so the result
+// does not depend on timing.  The walk is a chain of dependent loads: many short chains in flight hide
+// their latency.  Returns to the first kStatTokens threads only.
+constexpr int kStatTokens = 32, kStatParts = 8;
 struct TokenSums { float S, TZ; bool in_shift_range; };
+struct StatShared { float s[kStatParts][kStatTokens], t[kStatParts][kStatTokens], m[kStatParts][kStatTokens]; };
 
 __device__ __forceinline__ TokenSums token_sums(const float* __restrict__ s_part, const float* __restrict__ t_part,
-                                                int n_granules, int64_t ld, int kk, bool valid,
-                                                float (*s_s)[64], float (*t_s)[64], float (*m_s)[64]) {
-  const int t = threadIdx.x & 63, part = threadIdx.x >> 6;
+                                                int n_granules, int64_t ld, int kk, bool valid, StatShared& sh) {
+  const int t = threadIdx.x % kStatTokens, part = threadIdx.x / kStatTokens;
   float s = 0.f, tz = 0.f, mx = 0.f;
   if (valid) {
-    for (int gi = part; gi < n_granules; gi += 4) {
+#pragma unroll 8
+    for (int gi = part; gi < n_granules; gi += kStatParts) {
       const float v = s_part[(int64_t)gi * ld + kk];
       s += v;
       mx = fmaxf(mx, v);
     }
-    if (t_part)
-      for (int gi = part; gi < n_granules; gi += 4) tz += t_part[(int64_t)gi * ld + kk];
+    if (t_part) {
+#pragma unroll 8
+      for (int gi = part; gi < n_granules; gi += kStatParts) tz += t_part[(int64_t)gi * ld + kk];
+    }
   }
-  s_s[part][t] = s;
-  t_s[part][t] = tz;
-  m_s[part][t] = mx;
+  sh.s[part][t] = s;
+  sh.t[part][t] = tz;
+  sh.m[part][t] = mx;
   __syncthreads();
   TokenSums out;
-  out.S = (s_s[0][t] + s_s[1][t]) + (s_s[2][t] + s_s[3][t]);
-  out.TZ = (t_s[0][t] + t_s[1][t]) + (t_s[2][t] + t_s[3][t]);
-  out.in_shift_range = fmaxf(fmaxf(m_s[0][t], m_s[1][t]), fmaxf(m_s[2][t], m_s[3][t])) >= kShiftRangeLimit;
+  out.S = ((sh.s[0][t] + sh.s[1][t]) + (sh.s[2][t] + sh.s[3][t])) + ((sh.s[4][t] + sh.s[5][t]) + (sh.s[6][t] + sh.s[7][t]));
+  out.TZ = ((sh.t[0][t] + sh.t[1][t]) + (sh.t[2][t] + sh.t[3][t])) + ((sh.t[4][t] + sh.t[5][t]) + (sh.t[6][t] + sh.t[7][t]));
+  float m = sh.m[0][t];
+  for (int q = 1; q < kStatParts; ++q) m = fmaxf(m, sh.m[q][t]);
+  out.in_shift_range = m >= kShiftRangeLimit;
   return out;
 }
 
@@ -788,15 +813,14 @@ token_stats_kernel(const float* __restrict__ s_part, const float* __restrict__ t
                    const float* __restrict__ old_logp, const float* __restrict__ adv,
                    const int32_t* __restrict__ kept_seq, const float* __restrict__ kept_w,
                    float eps_lo, float eps_hi, float grad_scale, KlArgs klp,
-                   float* __restrict__ beta_out, float* __restrict__ patch_out,
+                   float* __restrict__ beta_out, uint16_t* __restrict__ Eb, int kb_z,
                    float* __restrict__ logp_out, float* __restrict__ kl_out, float* __restrict__ entropy_out,
                    float* __restrict__ term, int32_t* __restrict__ diag) {
-  __shared__ float s_s[4][64], t_s[4][64], m_s[4][64];
-  const int t = threadIdx.x & 63, part = threadIdx.x >> 6;
-  const int kk = blockIdx.x * 64 + t;
+  __shared__ StatShared sh;
+  const int kk = blockIdx.x * kStatTokens + threadIdx.x % kStatTokens;
   const bool valid = kk < n_valid;
-  const TokenSums sums = token_sums(s_part, t_part, n_granules, ld, kk, valid, s_s, t_s, m_s);
-  if (part != 0) return;                                 // wavefront 0 finishes the 64 tokens
+  const TokenSums sums = token_sums(s_part, t_part, n_granules, ld, kk, valid, sh);
+  if (threadIdx.x >= kStatTokens) return;                // the first threads finish the tokens
   bool bad_id = false, clipped = false, nonzero_adv = false;
   if (valid) {
     const float S = sums.S;
@@ -806,7 +830,6 @@ token_stats_kernel(const float* __restrict__ s_part, const float* __restrict__ t
     if (entropy_out) entropy_out[k] = logf(S) - sums.TZ / S;   // -sum_v p_v log p_v, p_v = E_v / S
     if (bad_id) {                                        // left out: no loss term, zero gradient
       beta_out[kk] = 0.f;
-      patch_out[kk] = 0.f;
       if (logp_out) logp_out[k] = __builtin_nanf("");
       if (kl_out) kl_out[k] = __builtin_nanf("");
       term[k] = 0.f;
@@ -820,7 +843,9 @@ token_stats_kernel(const float* __restrict__ s_part, const float* __restrict__ t
       clipped = ts.clipped;
       nonzero_adv = A != 0.f;
       beta_out[kk] = -ts.c / S;                          // dz_kv = beta_k E_kv off the target
-      patch_out[kk] = -S * (1.f - __expf(logp));         // E'_target with beta_k E' = c_k (1 - p_target)
+      // the target entry of E is replaced by E' with beta_k E' = c_k (1 - p_target): the two backward
+      // contractions then need no separate one-hot term
+      Eb[blk_off(kk, y, kb_z)] = f32_to_bf16_bits(-S * (1.f - __expf(logp)));
       if (logp_out) logp_out[k] = logp;
       if (kl_out) kl_out[k] = ts.kl;
       term[k] = w * ts.L;
@@ -840,12 +865,11 @@ logp_stats_kernel(const float* __restrict__ s_part, const float* __restrict__ t_
                   const float* __restrict__ ref, const float* __restrict__ z_target, int n_valid, int chunk_start,
                   const int32_t* __restrict__ ids, int V,
                   float* __restrict__ logp_out, float* __restrict__ entropy_out, int32_t* __restrict__ diag) {
-  __shared__ float s_s[4][64], t_s[4][64], m_s[4][64];
-  const int t = threadIdx.x & 63, part = threadIdx.x >> 6;
-  const int kk = blockIdx.x * 64 + t;
+  __shared__ StatShared sh;
+  const int kk = blockIdx.x * kStatTokens + threadIdx.x % kStatTokens;
   const bool valid = kk < n_valid;
-  const TokenSums sums = token_sums(s_part, t_part, n_granules, ld, kk, valid, s_s, t_s, m_s);
-  if (part != 0) return;
+  const TokenSums sums = token_sums(s_part, t_part, n_granules, ld, kk, valid, sh);
+  if (threadIdx.x >= kStatTokens) return;
   bool bad_id = false;
   if (valid) {
     const int k = chunk_start + kk;
@@ -860,24 +884,12 @@ logp_stats_kernel(const float* __restrict__ s_part, const float* __restrict__ t_
   }
 }
 
-// Overwrite the target entry of every valid token in E (see token_stats_kernel); a token whose id
-// lies outside [0, V) has no target entry.
-__global__ void __launch_bounds__(256)
-patch_target_kernel(uint16_t* __restrict__ Eb, int kb_z,
-                    const int32_t* __restrict__ ids, const float* __restrict__ patch, int n_valid, int V) {
-  const int kk = blockIdx.x * blockDim.x + threadIdx.x;
-  if (kk >= n_valid) return;
-  const int y = ids[kk];
-  if (y < 0 || y >= V) return;
-  Eb[blk_off(kk, y, kb_z)] = f32_to_bf16_bits(patch[kk]);
-}
-
 // -------------------------------------------------------------- host side ----
 static inline int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
 
 struct Bf16Plan {
   int64_t Vp, Hp; int n_granules; int cap;      // padded vocabulary / hidden size, granules, chunk capacity (tokens)
-  size_t off_Wb, off_Wtb, off_Hb, off_Hktb, off_Eb, off_s, off_t, off_zt, off_ref, off_beta, off_patch, off_term, off_dh_part, total;
+  size_t off_Wb, off_Wtb, off_Hb, off_Hktb, off_Eb, off_s, off_t, off_zt, off_ref, off_beta, off_term, off_dh_part, total;
 };
 
 static Bf16Plan make_plan(int32_t N_k, int32_t H, int32_t V, int cap) {
@@ -898,7 +910,6 @@ static Bf16Plan make_plan(int32_t N_k, int32_t H, int32_t V, int cap) {
   p.off_zt = take((size_t)cap * 4);
   p.off_ref = take((size_t)cap * 4);
   p.off_beta = take((size_t)cap * 4);
-  p.off_patch = take((size_t)cap * 4);
   p.off_term = take((size_t)(N_k > 0 ? N_k : 1) * 4);
   p.off_dh_part = take((size_t)kNumCU * kBM * kBN * 4);   // partial dH tiles of a split contraction (see dh_splits): 64 MiB
   p.total = off;
@@ -979,7 +990,6 @@ nat_status loss_bf16_run(const LossArgs& a) {
   float* zt = (float*)(ws + p.off_zt);
   float* ref = (float*)(ws + p.off_ref);
   float* beta = (float*)(ws + p.off_beta);
-  float* patch = (float*)(ws + p.off_patch);
   float* term = (float*)(ws + p.off_term);
   float* dh_part = (float*)(ws + p.off_dh_part);
   const uint16_t* W = (const uint16_t*)a.W;
@@ -1027,13 +1037,10 @@ nat_status loss_bf16_run(const LossArgs& a) {
       }
       {
         ProfScope prof(PC_TOKEN_STATS, s);
-        token_stats_kernel<<<(snv + 63) / 64, 256, 0, s>>>(s_part + s0, t_part ? t_part + s0 : nullptr, p.n_granules, cap,
-                                                          ref + s0, zt + s0, snv, c0 + s0, ids_s, V, a.old_logp, a.adv,
-                                                          a.kept_seq, a.kept_w, a.eps_lo, a.eps_hi, a.grad_scale,
-                                                          KlArgs{a.ref_logp, a.beta_kl, a.kl_kind}, beta + s0, patch + s0,
-                                                          a.logp, a.kl_out, a.entropy_out, term, a.diag);
-        NAT_LAUNCH_CHECK();
-        patch_target_kernel<<<(snv + 255) / 256, 256, 0, s>>>(Eb_s, Vp / 32, ids_s, patch + s0, snv, V);
+        token_stats_kernel<<<(snv + kStatTokens - 1) / kStatTokens, kStatTokens * kStatParts, 0, s>>>(
+            s_part + s0, t_part ? t_part + s0 : nullptr, p.n_granules, cap, ref + s0, zt + s0, snv, c0 + s0, ids_s, V,
+            a.old_logp, a.adv, a.kept_seq, a.kept_w, a.eps_lo, a.eps_hi, a.grad_scale,
+            KlArgs{a.ref_logp, a.beta_kl, a.kl_kind}, beta + s0, Eb_s, Vp / 32, a.logp, a.kl_out, a.entropy_out, term, a.diag);
         NAT_LAUNCH_CHECK();
       }
       {  // (diag(beta) H)^T of the sub-chunk into its k-slices of the chunk's blocked operand
@@ -1126,7 +1133,7 @@ nat_status logp_bf16_run(const LogpArgs& a) {
     }
     {
       ProfScope prof(PC_TOKEN_STATS, s);
-      logp_stats_kernel<<<(nv + 63) / 64, 256, 0, s>>>(s_part, t_part, p.n_granules, cap, ref, zt, nv, c0, a.ids + c0, V,
+      logp_stats_kernel<<<(nv + kStatTokens - 1) / kStatTokens, kStatTokens * kStatParts, 0, s>>>(s_part, t_part, p.n_granules, cap, ref, zt, nv, c0, a.ids + c0, V,
                                                       a.logp, a.entropy, a.diag);
       NAT_LAUNCH_CHECK();
     }

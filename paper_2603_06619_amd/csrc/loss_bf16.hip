@@ -224,6 +224,13 @@ struct TileLoader {
   __device__ __forceinline__ void issue_asm(char* lds_tile, int kt, int wave, int half) const {
     dma_2kib(src + (int64_t)kt * kBlkElems + half * 1024, lds_tile + wave * (kLoads * 1024) + half * 2048);
   }
+  // load kIdx = 0 .. kLoads - 1 of this wavefront's share
+  template <int kIdx>
+  __device__ __forceinline__ void issue_one(char* lds_tile, int kt, int wave) const {
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(src + (int64_t)kt * kBlkElems),
+                                     (__attribute__((address_space(3))) void*)(lds_tile + wave * (kLoads * 1024)), 16,
+                                     kIdx * 1024, 0);
+  }
   __device__ __forceinline__ void issue(char* lds_tile, int kt, int wave) const {
     const uint16_t* p = src + (int64_t)kt * kBlkElems;
     char* dst = lds_tile + wave * (kLoads * 1024);
@@ -320,6 +327,30 @@ __device__ __forceinline__ void interleave_reads() {
   }
 }
 
+// One k-substep of the row-major loop, instruction slot by slot (the compiler may not move anything
+// across a slot's end): slot m holds MFMA m on the fragments (au, bu); behind each of the first 4 + NB
+// MFMAs one fragment read of k-substep ks_load from (a_s, b_s) into (al, bl); the remaining MFMAs carry
+// the direct-to-LDS loads of this wavefront's share of slice k into lds_dst, evenly spaced (mixing them
+// with the fragment reads measured slower).
+template <int NW, int NB, int M = 0>
+__device__ __forceinline__ void substep_slots(f32x16 (&acc)[4][NB], const bf16x8 (&au)[4], const bf16x8 (&bu)[NB],
+                                              bf16x8 (&al)[4], bf16x8 (&bl)[NB], const char* a_s, const char* b_s,
+                                              int a_row0, int b_row0, int l32, int lhi, int ks_load,
+                                              const TileLoader<NW>& ld, char* lds_dst, int k, int wave) {
+  constexpr int kLoadFirst = 4 + NB, kLoadEvery = (4 * NB - kLoadFirst) / TileLoader<NW>::kLoads;
+  static_assert(kLoadEvery >= 1, "every load needs a slot");
+  if constexpr (M < 4 * NB) {
+    constexpr int i = M / NB, j = M % NB;
+    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(au[i], bu[j], acc[i][j], 0, 0, 0);
+    if constexpr (M < 4) al[M] = *(const bf16x8*)(a_s + lds_chunk_off(a_row0 + M * 32 + l32, ks_load * 2 + lhi));
+    else if constexpr (M < 4 + NB) bl[M - 4] = *(const bf16x8*)(b_s + lds_chunk_off(b_row0 + (M - 4) * 32 + l32, ks_load * 2 + lhi));
+    if constexpr (M >= kLoadFirst && (M - kLoadFirst) % kLoadEvery == 0 && (M - kLoadFirst) / kLoadEvery < TileLoader<NW>::kLoads)
+      ld.template issue_one<(M - kLoadFirst) / kLoadEvery>(lds_dst, k, wave);
+    __builtin_amdgcn_sched_barrier(0);
+    substep_slots<NW, NB, M + 1>(acc, au, bu, al, bl, a_s, b_s, a_row0, b_row0, l32, lhi, ks_load, ld, lds_dst, k, wave);
+  }
+}
+
 // fragments of k-substep ks: four 32-row blocks of A from row a_row0, NB 32-row blocks of B from b_row0
 template <int NB>
 __device__ __forceinline__ void load_frags(const char* a_s, const char* b_s, int a_row0, int b_row0, int l32, int lhi,
@@ -393,7 +424,8 @@ gemm_nt_kernel(GemmArgs g, Epilogue epi) {
   }
 
   if constexpr (AT) {
-    // The pipeline described below with the k-major A operand: fragments through the transposing read
+    // The pipeline described below (but with the whole refill under the last MFMAs of the second k-substep:
+    // splitting or spacing it measured 1-5 % slower here) with the k-major A operand: fragments through the transposing read
     // (two per fragment), refill loads through dma_2kib, 2 KiB per statement.  The compiler schedules the
     // fragment reads among the MFMAs as hinted; the refill statements are placed by hand behind the last
     // MFMAs of the second substep, one per MFMA.
@@ -452,81 +484,55 @@ gemm_nt_kernel(GemmArgs g, Epilogue epi) {
     __syncthreads();
     epi(acc, pre, m0 + a_row0, n0 + b_row0, lane, wave, &lds[0][0][0], split);
     return;
-  }
-
+  } else {
   // Software pipeline over k-slices of 32.  Slice kt lives in lds[kt % 4]; three slices are
-  // in flight while one is consumed, so a load has three iterations to land.  Loads complete
-  // in issue order, hence "slice kt+1 has landed" is vmcnt(2 * kLoadsPerWave): the two younger
-  // slices may still be outstanding.  The barrier sits before the second half of the slice's
-  // MFMAs, so the refill of the released buffer and the first fragment reads of the next slice
-  // issue under those MFMAs.  Slices past the end re-load the last one (harmless) to keep the
-  // body branch-free and the count fixed.
+  // in flight while one is consumed, so a load has two to three iterations to land.  The barrier
+  // sits between the two k-substeps of a slice; once it is passed, every wavefront has finished
+  // reading slice kt and its buffer may be refilled.  The refill is issued in two halves so that
+  // the loads of the NW wavefronts (which run in step) do not reach the CU's one address unit
+  // all within a few hundred cycles: the A tile under the second substep of slice kt, the B tile
+  // under the first substep of slice kt+1, each load one or two MFMAs after the previous one.
+  // Loads complete in issue order (A0 B0 A1 B1 ...), hence "slice kt+1 has landed" at the barrier of
+  // slice kt is vmcnt(2 * kLoadsPerWave): the halves of the two younger slices may be outstanding.
+  // Slices past the end re-load the last one (into a buffer nobody reads again) to keep the body
+  // branch-free and the count fixed.
+  constexpr int kHalfLoads = kLoadsPerWave / 2;                // loads per wavefront and operand tile
 #pragma unroll
   for (int st = 0; st < kStages; ++st) {
     const int k = st < kt_n ? st : kt_n - 1;
     la.issue(lds[st][0], k, wave);
-    lb.issue(lds[st][1], k, wave);
+    if (st < kStages - 1) lb.issue(lds[st][1], k, wave);
   }
-  __builtin_amdgcn_s_waitcnt(waitcnt_vm((kStages - 1) * kLoadsPerWave));
+  __builtin_amdgcn_s_waitcnt(waitcnt_vm((2 * kStages - 3) * kHalfLoads));   // slice 0 has landed
   __syncthreads();
   bf16x8 af[2][4], bfr[2][NB];
   load_frags<NB>(lds[0][0], lds[0][1], a_row0, b_row0, l32, lhi, 0, af[0], bfr[0]);
 
   for (int kt = 0; kt < kt_n; ++kt) {
-    const int cur = kt % kStages, nxt = (kt + 1) % kStages;
-    // first k-substep of slice kt; the second substep's fragments are read under its first MFMAs
-    load_frags<NB>(lds[cur][0], lds[cur][1], a_row0, b_row0, l32, lhi, 1, af[1], bfr[1]);
-    mfma_substep<NB>(acc, af[0], bfr[0]);
-#pragma unroll
-    for (int x = 0; x < kFragReads; ++x) {
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);     // 1 MFMA
-      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);     // 1 LDS read
-    }
-    __builtin_amdgcn_sched_group_barrier(0x008, kMfma - kFragReads, 0);
-    // keep all MFMAs of the first substep on this side of the barrier (their fragment
-    // registers are overwritten right after it)
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-      for (int j = 0; j < NB; ++j) asm volatile("" : "+a"(acc[i][j]));
+    const int cur = kt % kStages, nxt = (kt + 1) % kStages, last = (kt + kStages - 1) % kStages;
+    // first k-substep of slice kt; under its MFMAs: the second substep's fragments and the B half of
+    // the refill of the buffer released at the previous barrier (slice kt + 3)
+    int k1 = kt + kStages - 1;
+    k1 = k1 < kt_n ? k1 : kt_n - 1;
     __builtin_amdgcn_sched_barrier(0);
+    substep_slots<NW, NB>(acc, af[0], bfr[0], af[1], bfr[1], lds[cur][0], lds[cur][1], a_row0, b_row0, l32, lhi, 1,
+                          lb, lds[last][1], k1, wave);
     // slice kt+1 has landed (this wavefront's share; the barrier covers the others) and this
-    // wavefront has finished reading slice kt, whose buffer is refilled below
+    // wavefront has finished reading slice kt, whose buffer is refilled from here on
     __builtin_amdgcn_s_waitcnt(waitcnt_vm((kStages - 2) * kLoadsPerWave) & 0xf0ff);
     __builtin_amdgcn_s_barrier();
     __builtin_amdgcn_sched_barrier(0);
-    // second k-substep; under it: first fragments of slice kt+1, then the refill of lds[cur]
-    load_frags<NB>(lds[nxt][0], lds[nxt][1], a_row0, b_row0, l32, lhi, 0, af[0], bfr[0]);
-    mfma_substep<NB>(acc, af[1], bfr[1]);
-    {
-      int k2 = kt + kStages;
-      k2 = k2 < kt_n ? k2 : kt_n - 1;
-      la.issue(lds[cur][0], k2, wave);
-      lb.issue(lds[cur][1], k2, wave);
-    }
-#pragma unroll
-    for (int x = 0; x < kFragReads; ++x) {
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);     // 1 MFMA
-      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);     // 1 LDS read
-    }
-    if (NW == 4) {
-#pragma unroll
-      for (int x = 0; x < 8; ++x) {
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // 1 MFMA
-        __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);   // 1 global->LDS load
-      }
-    } else {
-#pragma unroll
-      for (int x = 0; x < 2; ++x) {
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // 1 MFMA
-        __builtin_amdgcn_sched_group_barrier(0x020, 2, 0);   // 2 global->LDS loads
-      }
-    }
+    // second k-substep; under it: first fragments of slice kt+1 and the A half of the refill of lds[cur]
+    int k2 = kt + kStages;
+    k2 = k2 < kt_n ? k2 : kt_n - 1;
+    substep_slots<NW, NB>(acc, af[1], bfr[1], af[0], bfr[0], lds[nxt][0], lds[nxt][1], a_row0, b_row0, l32, lhi, 0,
+                          la, lds[cur][0], k2, wave);
   }
   __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));   // no direct-to-LDS load may outlive the block
   __syncthreads();
 
   epi(acc, pre, m0 + a_row0, n0 + b_row0, lane, wave, &lds[0][0][0], split);
+  }
 }
 
 // ------------------------------------------------------------- epilogues ----

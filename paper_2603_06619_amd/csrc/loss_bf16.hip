@@ -75,6 +75,7 @@ constexpr int kTileBytes = kBM * kBK * 2;         // 16 KiB per operand per stag
 #endif
 constexpr int kMaxChunk = 32768;                  // token rows per chunk (recommended workspace)
 constexpr int kNumCU = 256;                       // compute units (one workgroup of these kernels each)
+constexpr int kMinSlicesPerRange = 32;            // shortest range of a cut dW contraction axis (k-slices)
 #ifndef NAT_SUBCHUNK
 #define NAT_SUBCHUNK 8192
 #endif
@@ -163,7 +164,9 @@ struct GemmArgs {
   int group_m;                // tile rows walked together (see tile_of_block)
   int kb_a_src;               // k-major A only (see TileLoaderKMajor): k-slices of the source operand
   int k_splits;               // > 1: the contraction axis is cut into this many ranges of kt_per_split k-slices, one
-  int kt_per_split;           // workgroup per (tile, range); the epilogue is told its range (row-major operands only)
+  int kt_per_split;           // workgroup per (tile, range); the epilogue is told which slab its raw sums go to
+  int tail_tiles;             // with k_splits > 1: 0 = every tile is cut (slab = range); T > 0 = only the last T tiles in
+                              // launch order are (slab = position among them * k_splits + range), the others run whole
 };
 
 // Block id -> output tile.  Blocks are dealt round-robin to the 8 XCDs, so ids
@@ -265,6 +268,7 @@ struct TileLoaderKMajor {
     src = base + (int64_t)(8 * tile + wave * kPieces) * kBlkElems + lane * 8;
     tile_stride = (int64_t)kb_src * kBlkElems;
   }
+  __device__ __forceinline__ void start_at(int kt0) { src += (int64_t)(kt0 >> 3) * tile_stride; }   // kt0 % 8 == 0
   __device__ __forceinline__ void issue(char* lds_tile, int kt, int wave) const {
 #pragma unroll
     for (int piece = 0; piece < kPieces; ++piece) issue_asm(lds_tile, kt, wave, piece);
@@ -387,8 +391,21 @@ gemm_nt_kernel(GemmArgs g, Epilogue epi) {
   __shared__ __attribute__((aligned(1024))) char lds[kStages][2][kTileBytes];
   int tm, tn;
   const int n_tiles = g.tiles_m * g.tiles_n;
-  const int split = g.k_splits > 1 ? (int)blockIdx.x / n_tiles : 0;
-  tile_of_block(g, (int)blockIdx.x - split * n_tiles, tm, tn);
+  int pid = (int)blockIdx.x, range = -1, slab = -1;           // range of the contraction axis / slab (-1: whole axis)
+  if (g.k_splits > 1) {
+    if (g.tail_tiles == 0) {
+      range = pid / n_tiles;
+      pid -= range * n_tiles;
+      slab = range;
+    } else if (pid >= n_tiles - g.tail_tiles) {
+      const int r = pid - (n_tiles - g.tail_tiles);
+      range = r / g.tail_tiles;
+      const int pos = r - range * g.tail_tiles;
+      pid = n_tiles - g.tail_tiles + pos;
+      slab = pos * g.k_splits + range;
+    }
+  }
+  tile_of_block(g, pid, tm, tn);
   const int m0 = tm * kBM, n0 = tn * kBN;
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -414,13 +431,11 @@ gemm_nt_kernel(GemmArgs g, Epilogue epi) {
   la.init(g.A, tm, AT ? g.kb_a_src : kt_all, wave, lane);
   lb.init(g.B, tn, kt_all, wave, lane);
   int kt_n = kt_all;                                           // k-slices this workgroup contracts over
-  if constexpr (!AT) {
-    if (g.k_splits > 1) {
-      const int kt0 = split * g.kt_per_split;
-      kt_n = kt_all - kt0 < g.kt_per_split ? kt_all - kt0 : g.kt_per_split;
-      la.start_at(kt0);
-      lb.start_at(kt0);
-    }
+  if (range >= 0) {
+    const int kt0 = range * g.kt_per_split;                    // a multiple of 8 (TileLoaderKMajor::start_at)
+    kt_n = kt_all - kt0 < g.kt_per_split ? kt_all - kt0 : g.kt_per_split;
+    la.start_at(kt0);
+    lb.start_at(kt0);
   }
 
   if constexpr (AT) {
@@ -482,7 +497,7 @@ gemm_nt_kernel(GemmArgs g, Epilogue epi) {
     }
     __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));   // no direct-to-LDS load may outlive the block
     __syncthreads();
-    epi(acc, pre, m0 + a_row0, n0 + b_row0, lane, wave, &lds[0][0][0], split);
+    epi(acc, pre, m0 + a_row0, n0 + b_row0, lane, wave, &lds[0][0][0], slab);
     return;
   } else {
   // Software pipeline over k-slices of 32.  Slice kt lives in lds[kt % 4]; three slices are
@@ -531,7 +546,7 @@ gemm_nt_kernel(GemmArgs g, Epilogue epi) {
   __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));   // no direct-to-LDS load may outlive the block
   __syncthreads();
 
-  epi(acc, pre, m0 + a_row0, n0 + b_row0, lane, wave, &lds[0][0][0], split);
+  epi(acc, pre, m0 + a_row0, n0 + b_row0, lane, wave, &lds[0][0][0], slab);
   }
 }
 
@@ -667,10 +682,10 @@ struct DHiddenEpilogue {
   template <int NB> __device__ __forceinline__ void prefetch(Pre<NB>&, int, int) const {}
   template <int NB>
   __device__ __forceinline__ void operator()(f32x16 (&acc)[4][NB], const Pre<NB>&, int k0, int h0, int lane, int,
-                                             char*, int split) const {
+                                             char*, int slab_id) const {
     const int l32 = lane & 31, lhi = lane >> 5;
-    if (partial) {                 // this workgroup's range of the vocabulary: the raw sums go to its slab
-      float* slab = partial + (int64_t)split * rows_p * cols_p;
+    if (slab_id >= 0) {            // this workgroup's range of the vocabulary: the raw sums go to its slab
+      float* slab = partial + (int64_t)slab_id * rows_p * cols_p;
 #pragma unroll
       for (int mb = 0; mb < 4; ++mb)
 #pragma unroll
@@ -701,13 +716,25 @@ struct DHiddenEpilogue {
 struct DWeightEpilogue {
   int V, H, accumulate;
   float* dW;                       // [V, H] fp32
+  float* partial;                  // tiles whose contraction is cut into ranges: [slab][256][256] fp32 raw sums
 
   template <int NB> struct Pre {};
   template <int NB> __device__ __forceinline__ void prefetch(Pre<NB>&, int, int) const {}
   template <int NB>
   __device__ __forceinline__ void operator()(f32x16 (&acc)[4][NB], const Pre<NB>&, int v0, int h0, int lane, int,
-                                             char*, int) const {
+                                             char*, int slab_id) const {
     const int l32 = lane & 31, lhi = lane >> 5;
+    if (slab_id >= 0) {            // one range of this tile's tokens: raw sums to the slab, added up by dw_tail_reduce_kernel
+      float* slab = partial + (int64_t)slab_id * (kBM * kBN);
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+        for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+          for (int r = 0; r < 16; ++r)
+            slab[((v0 & (kBM - 1)) + mb * 32 + 8 * (r >> 2) + 4 * lhi + (r & 3)) * kBN + (h0 & (kBN - 1)) + nb * 32 + l32] = acc[mb][nb][r];
+      return;
+    }
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) {
       const int h = h0 + nb * 32 + l32;
@@ -737,6 +764,26 @@ dh_reduce_kernel(const float* __restrict__ partial, int k_splits, int rows_p, in
   float s = 0.f;
   for (int sp = 0; sp < k_splits; ++sp) s += partial[sp * slab + (int64_t)k * cols_p + h];
   dH[(int64_t)k * H + h] = f32_to_bf16_bits(beta[k] * s);
+}
+
+// dW tiles of a launch whose last tail_tiles tiles (in launch order) were cut into k_splits ranges of tokens:
+// dW[v][h] (+)= slab 0 + slab 1 + ... of the tile, in range order.  One block per 1024 elements of a tile.
+__global__ void __launch_bounds__(256)
+dw_tail_reduce_kernel(const float* __restrict__ partial, GemmArgs g, int V, int H, int accumulate, float* __restrict__ dW) {
+  const int pos = blockIdx.y;
+  int tm, tn;
+  tile_of_block(g, g.tiles_m * g.tiles_n - g.tail_tiles + pos, tm, tn);
+  const float* slab = partial + (int64_t)pos * g.k_splits * (kBM * kBN);
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    const int e = (blockIdx.x * 4 + q) * 256 + threadIdx.x;
+    const int v = tm * kBM + e / kBN, h = tn * kBN + e % kBN;
+    if (v >= V || h >= H) continue;
+    float sum = 0.f;
+    for (int r = 0; r < g.k_splits; ++r) sum += slab[(int64_t)r * (kBM * kBN) + e];
+    float* p = dW + (int64_t)v * H + h;
+    *p = accumulate ? *p + sum : sum;
+  }
 }
 
 // ----------------------------------------------------- reference logit ----
@@ -917,7 +964,7 @@ static Bf16Plan make_plan(int32_t N_k, int32_t H, int32_t V, int cap) {
   p.off_ref = take((size_t)cap * 4);
   p.off_beta = take((size_t)cap * 4);
   p.off_term = take((size_t)(N_k > 0 ? N_k : 1) * 4);
-  p.off_dh_part = take((size_t)kNumCU * kBM * kBN * 4);   // partial dH tiles of a split contraction (see dh_splits): 64 MiB
+  p.off_dh_part = take((size_t)kNumCU * kBM * kBN * 4);   // raw fp32 tiles of a contraction cut into ranges (dH, or the last dW tiles): 64 MiB
   p.total = off;
   return p;
 }
@@ -1080,10 +1127,31 @@ nat_status loss_bf16_run(const LossArgs& a) {
     }
     {  // dW: rows = vocabulary, columns = hidden units, contraction over the chunk's (padded) tokens
       // A = E from its one copy (rows = token), i.e. stored along this contraction's k axis
-      GemmArgs g{Eb, Hktb, np, Vp / kBM, Hp / kBN, NAT_GROUP_DWEIGHT, Vp / 32};
-      DWeightEpilogue e{V, H, (c0 > 0 || a.accumulate_dw) ? 1 : 0, a.dW};
-      nat_status st = launch_gemm<NAT_WAVES_DWEIGHT, DWeightEpilogue, true>(g, e, PC_DWEIGHT, s);
-      if (st != NAT_OK) return st;
+      // The tiles left over after the last full round of one tile per compute unit would occupy a fraction
+      // of the chip for a whole tile time: their token axis is cut into ranges (one workgroup per tile and
+      // range, raw sums to slabs) that are added into dW in range order afterwards.
+      const int tiles = (Vp / kBM) * (Hp / kBN), kt_all = np / kBK;
+      const int tail = tiles % kNumCU;
+      int splits = (tail > 0 && tail * 2 <= kNumCU) ? kNumCU / tail : 1, kt_per = kt_all;
+      if (splits > 8) splits = 8;
+      while (splits > 1 && kt_all / splits < kMinSlicesPerRange) --splits;
+      if (splits > 1) {
+        kt_per = (int)round_up((kt_all + splits - 1) / splits, 8);
+        splits = (kt_all + kt_per - 1) / kt_per;               // every range non-empty
+      }
+      const int accumulate = (c0 > 0 || a.accumulate_dw) ? 1 : 0;
+      GemmArgs g{Eb, Hktb, np, Vp / kBM, Hp / kBN, NAT_GROUP_DWEIGHT, Vp / 32, splits, kt_per, splits > 1 ? tail : 0};
+      DWeightEpilogue e{V, H, accumulate, a.dW, dh_part};
+      {
+        ProfScope prof(PC_DWEIGHT, s);
+        const int grid = splits > 1 ? tiles - tail + tail * splits : tiles;
+        gemm_nt_kernel<DWeightEpilogue, NAT_WAVES_DWEIGHT, true><<<grid, NAT_WAVES_DWEIGHT * 64, 0, s>>>(g, e);
+        NAT_LAUNCH_CHECK();
+        if (splits > 1) {
+          dw_tail_reduce_kernel<<<dim3(kBM * kBN / 1024, tail), 256, 0, s>>>(dh_part, g, V, H, accumulate, a.dW);
+          NAT_LAUNCH_CHECK();
+        }
+      }
     }
   }
   ProfScope prof(PC_LOSS_REDUCE, s);

@@ -199,6 +199,25 @@ def test_bf16_hidden_size_not_a_multiple_of_the_tile(stage):
     check(out, ref, 300, TOL_BF16, case)
 
 
+def test_bf16_dw_leftover_tiles_cut_into_token_ranges(stage):
+    # 8 dW tiles on 256 compute units: all of them are "left over" after the last full round, so the library
+    # cuts their token axis (8173 tokens = 256 k-slices) into 8 ranges and adds the partial tiles in range
+    # order; checked against the oracle element by element, with and without accumulation, and bit for bit
+    # between two runs
+    n_tok, H, V = 8192 - 19, 256, 2048
+    case = make_loss_case(55, n_tok, H, V, "bf16", noise=0.1, w_std=0.1)
+    ref = oracle_loss(**case)
+    out = hip_loss(stage, case, "bf16")
+    check(out, ref, n_tok, TOL_BF16, case, label="dW tiles in 8 token ranges")
+    first = out["dW"].clone()
+    b0 = float(np.abs(ref["dW"]).max())
+    base = torch.full((V, H), b0, dtype=torch.float32, device=DEV)
+    out2 = hip_loss(stage, case, "bf16", dW=base.clone(), accumulate_dw=True)
+    assert max_rel_err(out2["dW"].cpu().numpy() - np.float32(b0), ref["dW"]) <= TOL_BF16
+    again = hip_loss(stage, case, "bf16")
+    assert torch.equal(first, again["dW"])
+
+
 def test_bf16_full_vocabulary_mid_size_every_element_of_dw(stage):
     # the whole vocabulary (V = 151936, H = 1024) with enough tokens for 9 token tiles, and a workspace
     # that forces 3 chunks: dW (and everything else) against the oracle element by element
@@ -210,7 +229,8 @@ def test_bf16_full_vocabulary_mid_size_every_element_of_dw(stage):
     assert ws < nat.loss_workspace_bytes(1024, H, V, nat.DTYPE_BF16)
     out = hip_loss(stage, case, "bf16", ws_bytes=ws)
     check(out, ref, n_tok, TOL_BF16, case, label="full vocabulary, H = 1024, %d tokens in 3 chunks" % n_tok)
-    # one chunk gives the same log-probs bit for bit and dW within rounding of the chunked sum
+    # one chunk gives the same log-probs bit for bit and dW within rounding of the chunked sum (with one chunk
+    # the 72 dW tiles left over after 9 full rounds are cut into two token ranges)
     one = hip_loss(stage, case, "bf16")
     assert torch.equal(one["logp"][:n_tok], out["logp"][:n_tok])
     check(one, ref, n_tok, TOL_BF16, case, label="same, one chunk")

@@ -567,16 +567,17 @@ struct LogitsEpilogue {
 
   static constexpr int kStageRow = 272;        // bytes per token row of the LDS staging tile (128 bf16 + pad)
 
+  // Raw loads only, from a clamped index and without a use: nothing here waits for memory, so the
+  // operand loads of the k-loop are issued right behind these (n_valid >= 1 in every launch).
   template <int NB> struct Pre { int y[NB]; float shift[NB]; };
   template <int NB>
   __device__ __forceinline__ void prefetch(Pre<NB>& pre, int k0, int lane) const {
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) {
       const int kk = k0 + nb * 32 + (lane & 31);
-      const bool tok_valid = kk < n_valid;
-      const int y = tok_valid ? ids[kk] : -1;
-      pre.y[nb] = (y >= 0 && y < V) ? y : -1;              // an id outside the vocabulary matches no row
-      pre.shift[nb] = tok_valid ? ref[kk] : 0.f;
+      const int kc = kk < n_valid ? kk : n_valid - 1;
+      pre.y[nb] = ids[kc];
+      pre.shift[nb] = ref[kc];
     }
   }
 
@@ -589,10 +590,19 @@ struct LogitsEpilogue {
     const bool all_rows_valid = v0 + kGranule <= V;
     constexpr float kLog2e = 1.44269504088896340736f, kLn2 = 0.69314718055994530942f;
 
+    int y_of[NB];                  // target id of this lane's token per column block; -1: padding column, or
+    float shift_of[NB];            // an id outside the vocabulary (matches no row)
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) {
+      const bool tok_valid = k0 + nb * 32 + l32 < n_valid;
+      y_of[nb] = (tok_valid && pre.y[nb] >= 0 && pre.y[nb] < V) ? pre.y[nb] : -1;
+      shift_of[nb] = tok_valid ? pre.shift[nb] : 0.f;
+    }
+
     // exact target logit, if the target row lies in this granule and in this lane's half
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) {
-      const int yrel = pre.y[nb] - v0;
+      const int yrel = y_of[nb] - v0;
       if (__any(yrel >= 0 && yrel < kGranule)) {
         if (yrel >= 0 && yrel < kGranule && ((yrel >> 2) & 1) == lhi) {
           float zt = 0.f;
@@ -620,7 +630,7 @@ struct LogitsEpilogue {
     char* stage = lds + wave * (32 * kStageRow);
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) {
-      const float nshift2 = -pre.shift[nb] * kLog2e;
+      const float nshift2 = -shift_of[nb] * kLog2e;
       float s2[2] = {0.f, 0.f}, t2[2] = {0.f, 0.f};        // two independent chains per sum
 #pragma unroll
       for (int mb = 0; mb < 4; ++mb) {

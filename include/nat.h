@@ -321,7 +321,9 @@ size_t nat_loss_workspace_min_bytes(int32_t N_k, int32_t H, int32_t V, int32_t d
  *   d_ids_k [N_k] int32 in [0, V);  d_old_logp_k [N_k] float;  d_adv [>= max(kept_seq)+1] float;
  *   d_loss [1] float out;  d_logp_k [N_k] float out or NULL;
  *   d_dH_k [N_k, H] out, same dtype as the inputs;
- *   d_dW [V, H] float32 out: overwritten, or added to when accumulate_dw != 0.
+ *   d_dW [V, H] float32 out: overwritten, or added to when accumulate_dw != 0.  Ordinary device memory
+ *     (hipMalloc or a sub-range of it), not host-coherent / fine-grained memory: chunks after the first are
+ *     added with the GPU's fp32 memory atomics (one addition per element and chunk, chunks in stream order).
  *   The reduction order of d_dW and d_loss is fixed: results are bit-identical from run to run.
  *   The [N_k, V] logits are never written to memory as a whole; the bf16 path keeps the bf16
  *   soft-max numerators exp(z - z_target) of one token chunk (at most 32768 tokens) in the

@@ -756,7 +756,10 @@ struct DWeightEpilogue {
           const int v = v0 + mb * 32 + 8 * (r >> 2) + 4 * lhi + (r & 3);
           if (v < V) {
             float* p = dW + (int64_t)v * H + h;
-            *p = accumulate ? *p + acc[mb][nb][r] : acc[mb][nb][r];
+            // one owner per element and launch, launches in stream order: the sum is the same as a
+            // read-modify-write, but the addition happens at the L2 and the workgroup does not wait for it
+            if (accumulate) unsafeAtomicAdd(p, acc[mb][nb][r]);
+            else *p = acc[mb][nb][r];
           }
         }
     }

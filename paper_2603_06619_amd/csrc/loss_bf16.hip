@@ -302,15 +302,15 @@ struct KMajorFragOffsets {
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef short s16x8 __attribute__((ext_vector_type(8)));
 
-// fragments of k-substep ks with A in the k-major tile: four 32-row blocks from block a_blk0 (two
+// fragments of k-substep ks with A in the k-major tile: MA 32-row blocks from block a_blk0 (two
 // transposing reads each), NB blocks of B
-template <int NB>
+template <int MA, int NB>
 __device__ __forceinline__ void load_frags_kmajor(const char* a_s, const char* b_s, int a_blk0, int b_row0, int l32, int lhi,
-                                                  const KMajorFragOffsets& fo, int ks, bf16x8 (&af)[4], bf16x8 (&bfr)[NB]) {
+                                                  const KMajorFragOffsets& fo, int ks, bf16x8 (&af)[MA], bf16x8 (&bfr)[NB]) {
 #pragma unroll
   for (int j = 0; j < NB; ++j) bfr[j] = *(const bf16x8*)(b_s + lds_chunk_off(b_row0 + j * 32 + l32, ks * 2 + lhi));
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
+  for (int i = 0; i < MA; ++i) {
     const char* piece = a_s + (a_blk0 + i) * 2048 + ks * 1024;
     const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(piece + fo.off[0]));
     const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(piece + fo.off[1]));
@@ -444,11 +444,26 @@ gemm_nt_kernel(GemmArgs g, Epilogue epi) {
     // (two per fragment), refill loads through dma_2kib, 2 KiB per statement.  The compiler schedules the
     // fragment reads among the MFMAs as hinted; the refill statements are placed by hand behind the last
     // MFMAs of the second substep, one per MFMA.
+    // The transposing read delivers half the bytes per clock of a 16-byte read (measured: ~110 against
+    // ~256 bytes per clock and CU), so with 8 wavefronts the wavefront tile is 64 rows of A by 128 columns
+    // of B: the A tile is then read by two wavefronts and the B tile by four, instead of four and two.
+    constexpr int MA = NW == 8 ? 2 : 4;                    // 32-row blocks of A per wavefront
+    constexpr int NT = 64 / (NW * MA);                     // 32-column blocks of B per wavefront (4)
+    constexpr int kWavesN = 8 / NT;                        // wavefronts along the columns
+    const int a_rowT = (wave / kWavesN) * (MA * 32), b_rowT = (wave % kWavesN) * (NT * 32);
+    constexpr int kMfmaT = MA * NT;                        // MFMAs per k-substep
     constexpr int kDma = kLoadsPerWave / 2;                // refill statements per wavefront and slice (4 or 2)
-    constexpr int kReads = 8 + NB;                         // LDS reads per k-substep
+    constexpr int kReads = 2 * MA + NT;                    // LDS reads per k-substep
+    f32x16 accT[MA][NT];
+#pragma unroll
+    for (int i = 0; i < MA; ++i)
+#pragma unroll
+      for (int j = 0; j < NT; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) accT[i][j][r] = 0.f;
     KMajorFragOffsets fo;
     fo.init(lane);
-    const int a_blk0 = a_row0 / 32;
+    const int a_blk0 = a_rowT / 32;
     auto refill = [&](int st, int k, int d) {              // statement d of the refill of stage st with slice k
       if (d < kDma / 2) la.issue_asm(lds[st][0], k, wave, d);
       else lb.issue_asm(lds[st][1], k, wave, d - kDma / 2);
@@ -459,19 +474,21 @@ gemm_nt_kernel(GemmArgs g, Epilogue epi) {
       for (int d = 0; d < kDma; ++d) refill(st, st < kt_n ? st : kt_n - 1, d);
     __builtin_amdgcn_s_waitcnt(waitcnt_vm((kStages - 1) * kLoadsPerWave));
     __syncthreads();
-    bf16x8 af[2][4], bfr[2][NB];
-    load_frags_kmajor<NB>(lds[0][0], lds[0][1], a_blk0, b_row0, l32, lhi, fo, 0, af[0], bfr[0]);
+    bf16x8 af[2][MA], bfr[2][NT];
+    load_frags_kmajor<MA, NT>(lds[0][0], lds[0][1], a_blk0, b_rowT, l32, lhi, fo, 0, af[0], bfr[0]);
 
     for (int kt = 0; kt < kt_n; ++kt) {
       const int cur = kt % kStages, nxt = (kt + 1) % kStages;
       // first k-substep of slice kt; the second substep's fragments are read under its MFMAs
-      load_frags_kmajor<NB>(lds[cur][0], lds[cur][1], a_blk0, b_row0, l32, lhi, fo, 1, af[1], bfr[1]);
-      mfma_substep<NB>(acc, af[0], bfr[0]);
-      interleave_reads<kMfma, kReads>();
+      load_frags_kmajor<MA, NT>(lds[cur][0], lds[cur][1], a_blk0, b_rowT, l32, lhi, fo, 1, af[1], bfr[1]);
 #pragma unroll
-      for (int i = 0; i < 4; ++i)
+      for (int m = 0; m < kMfmaT; ++m)
+        accT[m / NT][m % NT] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[0][m / NT], bfr[0][m % NT], accT[m / NT][m % NT], 0, 0, 0);
+      interleave_reads<kMfmaT, kReads>();
 #pragma unroll
-        for (int j = 0; j < NB; ++j) asm volatile("" : "+a"(acc[i][j]));
+      for (int i = 0; i < MA; ++i)
+#pragma unroll
+        for (int j = 0; j < NT; ++j) asm volatile("" : "+a"(accT[i][j]));
       __builtin_amdgcn_sched_barrier(0);
       // slice kt+1 has landed (this wavefront's share; the barrier covers the others) and this wavefront
       // has finished reading slice kt, whose buffer is refilled below
@@ -479,25 +496,25 @@ gemm_nt_kernel(GemmArgs g, Epilogue epi) {
       __builtin_amdgcn_s_barrier();
       __builtin_amdgcn_sched_barrier(0);
       // second k-substep; under it the first fragments of slice kt+1, then the refill of lds[cur]
-      load_frags_kmajor<NB>(lds[nxt][0], lds[nxt][1], a_blk0, b_row0, l32, lhi, fo, 0, af[0], bfr[0]);
+      load_frags_kmajor<MA, NT>(lds[nxt][0], lds[nxt][1], a_blk0, b_rowT, l32, lhi, fo, 0, af[0], bfr[0]);
       int k2 = kt + kStages;
       k2 = k2 < kt_n ? k2 : kt_n - 1;
-      constexpr int kHead = kMfma - kDma;                  // MFMAs that carry the fragment reads
+      constexpr int kHead = kMfmaT - kDma;                 // MFMAs that carry the fragment reads
 #pragma unroll
       for (int m = 0; m < kHead; ++m)
-        acc[m / NB][m % NB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[1][m / NB], bfr[1][m % NB], acc[m / NB][m % NB], 0, 0, 0);
+        accT[m / NT][m % NT] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[1][m / NT], bfr[1][m % NT], accT[m / NT][m % NT], 0, 0, 0);
       interleave_reads<kHead, kReads>();
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-      for (int m = kHead; m < kMfma; ++m) {
-        acc[m / NB][m % NB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[1][m / NB], bfr[1][m % NB], acc[m / NB][m % NB], 0, 0, 0);
+      for (int m = kHead; m < kMfmaT; ++m) {
+        accT[m / NT][m % NT] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[1][m / NT], bfr[1][m % NT], accT[m / NT][m % NT], 0, 0, 0);
         refill(cur, k2, m - kHead);
         __builtin_amdgcn_sched_barrier(0);
       }
     }
     __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));   // no direct-to-LDS load may outlive the block
     __syncthreads();
-    epi(acc, pre, m0 + a_row0, n0 + b_row0, lane, wave, &lds[0][0][0], slab);
+    epi(accT, pre, m0 + a_rowT, n0 + b_rowT, lane, wave, &lds[0][0][0], slab);
     return;
   } else {
   // Software pipeline over k-slices of 32.  Slice kt lives in lds[kt % 4]; three slices are
@@ -730,8 +747,9 @@ struct DWeightEpilogue {
 
   template <int NB> struct Pre {};
   template <int NB> __device__ __forceinline__ void prefetch(Pre<NB>&, int, int) const {}
-  template <int NB>
-  __device__ __forceinline__ void operator()(f32x16 (&acc)[4][NB], const Pre<NB>&, int v0, int h0, int lane, int,
+  // the wavefront's tile is MA x NB blocks of 32 x 32 (see the k-major branch of gemm_nt_kernel)
+  template <int MA, int NB, class P>
+  __device__ __forceinline__ void operator()(f32x16 (&acc)[MA][NB], const P&, int v0, int h0, int lane, int,
                                              char*, int slab_id) const {
     const int l32 = lane & 31, lhi = lane >> 5;
     if (slab_id >= 0) {            // one range of this tile's tokens: raw sums to the slab, added up by dw_tail_reduce_kernel
@@ -739,7 +757,7 @@ struct DWeightEpilogue {
 #pragma unroll
       for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
-        for (int mb = 0; mb < 4; ++mb)
+        for (int mb = 0; mb < MA; ++mb)
 #pragma unroll
           for (int r = 0; r < 16; ++r)
             slab[((v0 & (kBM - 1)) + mb * 32 + 8 * (r >> 2) + 4 * lhi + (r & 3)) * kBN + (h0 & (kBN - 1)) + nb * 32 + l32] = acc[mb][nb][r];
@@ -750,7 +768,7 @@ struct DWeightEpilogue {
       const int h = h0 + nb * 32 + l32;
       if (h >= H) continue;
 #pragma unroll
-      for (int mb = 0; mb < 4; ++mb)
+      for (int mb = 0; mb < MA; ++mb)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
           const int v = v0 + mb * 32 + 8 * (r >> 2) + 4 * lhi + (r & 3);

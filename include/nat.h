@@ -326,8 +326,9 @@ size_t nat_loss_workspace_min_bytes(int32_t N_k, int32_t H, int32_t V, int32_t d
  *     added with the GPU's fp32 memory atomics (one addition per element and chunk, chunks in stream order).
  *   The reduction order of d_dW and d_loss is fixed: results are bit-identical from run to run.
  *   The [N_k, V] logits are never written to memory as a whole; the bf16 path keeps the bf16
- *   soft-max numerators exp(z - z_target) of one token chunk (at most 32768 tokens) in the
- *   workspace.  That shift requires log(p_max / p_target) < 70 for every kept token (larger
+ *   soft-max numerators exp(z - z_target) of one token chunk (16384 tokens with the recommended
+ *   workspace, 32768 for hidden sizes whose dH launch would not fill whole rounds of workgroups at
+ *   16384; fewer with a smaller workspace) in the workspace.  That shift requires log(p_max / p_target) < 70 for every kept token (larger
  *   numerators are clamped; nat_loss_fwd_bwd_kl counts the tokens this may have touched); the
  *   fp32 path has no such bound.  A token whose id lies outside [0, V) is left out of loss, dH
  *   and dW (nat_loss_fwd_bwd_kl counts those too).

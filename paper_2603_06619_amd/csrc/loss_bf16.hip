@@ -4,7 +4,7 @@
 // (App. A) on the kept tokens.  The forward pass alone runs the first two steps below and
 // keeps only the sums.
 //
-// Tokens are processed in chunks of at most `cap` rows (32768 with the recommended workspace); the
+// Tokens are processed in chunks of at most `cap` rows (16384 or 32768 with the recommended workspace); the
 // forward sweep and the dH contraction of a chunk run in sub-chunks of 8192 rows.  Per chunk:
 //   reference     ref_k = h_k . W[ids_k]: the target logit, used only as the exponent shift;
 //   logits GEMM   Z^T tile = W_tile . H^T on bf16 MFMA with fp32 accumulators; the epilogue never
@@ -73,7 +73,7 @@ constexpr int kTileBytes = kBM * kBK * 2;         // 16 KiB per operand per stag
 #ifndef NAT_WAVES_DWEIGHT
 #define NAT_WAVES_DWEIGHT 8
 #endif
-constexpr int kMaxChunk = 32768;                  // token rows per chunk (recommended workspace)
+constexpr int kMaxChunk = 32768;                  // most token rows per chunk (see recommended_cap)
 constexpr int kNumCU = 256;                       // compute units (one workgroup of these kernels each)
 constexpr int kMinSlicesPerRange = 32;            // shortest range of a cut dW contraction axis (k-slices)
 #ifndef NAT_SUBCHUNK
@@ -1015,13 +1015,25 @@ static int sub_chunk_rows(int cap, int Hp) {
   return cap;
 }
 
-static int recommended_cap(int32_t N_k) {
-  int64_t cap = round_up(N_k > 0 ? N_k : 1, kBN);
-  return (int)(cap > kMaxChunk ? kMaxChunk : cap);
+// Chunk capacity of the recommended workspace.  Forward pass alone: kMaxChunk.  With the backward pass the
+// chunk also sizes the stored soft-max numerators (cap x Vp x 2 bytes), and the dW contraction, whose
+// contraction axis is the chunk, is within 0.2 % of its 32768-token speed at 16384 (measured): the
+// smallest of 16384 / 24576 / 32768 rows whose dH launch fills whole rounds of workgroups to 97 %.
+static int recommended_cap(int32_t N_k, int32_t H, bool backward) {
+  const int64_t all = round_up(N_k > 0 ? N_k : 1, kBN);
+  if (!backward) return (int)(all > kMaxChunk ? kMaxChunk : all);
+  if (all <= kMaxChunk / 2) return (int)all;
+  const int n_col = (int)(round_up(H, kBN) / kBN);
+  for (int cap = kMaxChunk / 2; cap < kMaxChunk; cap += kMaxChunk / 4) {
+    const int tiles = cap / kBM * n_col;
+    const int waves = (tiles + kNumCU - 1) / kNumCU;
+    if (tiles * 100 >= waves * kNumCU * 97) return (int)(all < cap ? all : cap);
+  }
+  return (int)(all > kMaxChunk ? kMaxChunk : all);
 }
 
 size_t loss_bf16_workspace_bytes(int32_t N_k, int32_t H, int32_t V, bool minimal) {
-  return make_plan(N_k, H, V, minimal ? kBN : recommended_cap(N_k)).total;
+  return make_plan(N_k, H, V, minimal ? kBN : recommended_cap(N_k, H, true)).total;
 }
 
 // workspace of the forward pass alone: W and H_chunk blocked, the partial sums, two per-token vectors
@@ -1045,7 +1057,7 @@ static FwdPlan make_fwd_plan(int32_t H, int32_t V, int cap) {
 }
 
 size_t logp_bf16_workspace_bytes(int32_t N_k, int32_t H, int32_t V, bool minimal) {
-  return make_fwd_plan(H, V, minimal ? kBN : recommended_cap(N_k)).total;
+  return make_fwd_plan(H, V, minimal ? kBN : recommended_cap(N_k, H, false)).total;
 }
 
 template <int NW, class Epi, bool AT = false>
@@ -1058,7 +1070,7 @@ static nat_status launch_gemm(const GemmArgs& g, const Epi& epi, int prof_class,
 
 nat_status loss_bf16_run(const LossArgs& a) {
   // largest chunk capacity (multiple of 256 tokens) whose plan fits the workspace
-  int cap = recommended_cap(a.N_k);
+  int cap = recommended_cap(a.N_k, a.H, true);
   while (cap > kBN && make_plan(a.N_k, a.H, a.V, cap).total > a.ws_bytes) cap -= kBN;
   const Bf16Plan p = make_plan(a.N_k, a.H, a.V, cap);
   if (p.total > a.ws_bytes) return NAT_WORKSPACE_TOO_SMALL;
@@ -1193,7 +1205,7 @@ nat_status loss_bf16_run(const LossArgs& a) {
 
 
 nat_status logp_bf16_run(const LogpArgs& a) {
-  int cap = recommended_cap(a.N_k);
+  int cap = recommended_cap(a.N_k, a.H, false);
   while (cap > kBN && make_fwd_plan(a.H, a.V, cap).total > a.ws_bytes) cap -= kBN;
   const FwdPlan p = make_fwd_plan(a.H, a.V, cap);
   if (p.total > a.ws_bytes) return NAT_WORKSPACE_TOO_SMALL;

@@ -147,7 +147,7 @@ def test_sampled_tokens_with_kl_term_and_entropy_at_full_size(full_run):
                               sc["kept_w"], nk, ref_logp_k=ref_lp, beta_kl=0.04, kl_kind=ogrpo.KL_NONNEG,
                               want_kl=True, want_entropy=True)
     torch.cuda.synchronize()
-    sample = np.unique(np.concatenate([[0, 255, 256, nk - 1, 32767, 32768], np.random.default_rng(1).integers(0, nk, 14)]))
+    sample = np.unique(np.concatenate([[0, 255, 256, nk - 1, 16383, 16384, 32767, 32768], np.random.default_rng(1).integers(0, nk, 14)]))
     sample = sample[sample < nk]
     sidx = torch.from_numpy(sample).to(DEV)
     adv = full_run["adv"].cpu().numpy().astype(np.float64)

@@ -59,7 +59,7 @@ def test_full_size_workload_sampled_tokens(name, mode, kw):
     assert np.array_equal(sc["kept_idx"][:nk].cpu().numpy(), kept_ref)
     # sampled kept tokens through the oracle
     rng = np.random.default_rng(3)
-    sample = np.unique(np.concatenate([[0, nk - 1, min(32767, nk - 1), min(32768, nk - 1)], rng.integers(0, nk, 12)]))
+    sample = np.unique(np.concatenate([[0, nk - 1, min(16383, nk - 1), min(16384, nk - 1), min(32767, nk - 1), min(32768, nk - 1)], rng.integers(0, nk, 12)]))
     sidx = torch.from_numpy(sample).to(DEV)
     ref = ogrpo.loss_and_grads(sc["hidden_k"][sidx].float().cpu().numpy(), b["W"].float().cpu().numpy(),
                                sc["ids_k"][sidx].cpu().numpy(), sc["old_logp_k"][sidx].cpu().numpy(),

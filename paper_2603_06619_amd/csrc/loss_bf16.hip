@@ -388,7 +388,16 @@ gemm_nt_kernel(GemmArgs g, Epilogue epi) {
   constexpr int NB = 16 / NW;                                  // 32-column blocks per wavefront
   constexpr int kLoadsPerWave = 2 * (kTileBytes / 1024) / NW;  // direct-to-LDS loads per wavefront per slice
   constexpr int kMfma = 4 * NB, kFragReads = 4 + NB;           // per k-substep
-  __shared__ __attribute__((aligned(1024))) char lds[kStages][2][kTileBytes];
+  // one LDS object (with a second one the compiler's wait-count pass orders every fragment read behind all
+  // direct-to-LDS loads in flight): the ring, and behind it the words the epilogue parks across the k-loop
+  constexpr int kStashWords = Epilogue::template stash_words<16 / NW>();
+  struct Shared {
+    char ring[kStages][2][kTileBytes];
+    int stash[kStashWords > 0 ? kStashWords * NW * 64 : 1];
+  };
+  __shared__ __attribute__((aligned(1024))) Shared sm;
+  auto& lds = sm.ring;
+  int* pre_stash = sm.stash;
   int tm, tn;
   const int n_tiles = g.tiles_m * g.tiles_n;
   int pid = (int)blockIdx.x, range = -1, slab = -1;           // range of the contraction axis / slab (-1: whole axis)
@@ -421,9 +430,9 @@ gemm_nt_kernel(GemmArgs g, Epilogue epi) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-  // per-column scalars the epilogue needs (token id, exponent shift): fetched now, used after the k-loop
+  // per-column scalars the epilogue needs (token id, exponent shift): fetched into LDS now, read after the k-loop
   typename Epilogue::template Pre<NB> pre;
-  epi.prefetch(pre, n0 + b_row0, lane);
+  epi.template prefetch<NB>(pre_stash, NW * 64, n0 + b_row0, lane, wave);
 
   typename std::conditional<AT, TileLoaderKMajor<NW>, TileLoader<NW>>::type la;
   TileLoader<NW> lb;
@@ -563,6 +572,7 @@ gemm_nt_kernel(GemmArgs g, Epilogue epi) {
   __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));   // no direct-to-LDS load may outlive the block
   __syncthreads();
 
+  epi.unstash(pre, pre_stash, NW * 64);
   epi(acc, pre, m0 + a_row0, n0 + b_row0, lane, wave, &lds[0][0][0], slab);
   }
 }
@@ -584,17 +594,32 @@ struct LogitsEpilogue {
 
   static constexpr int kStageRow = 272;        // bytes per token row of the LDS staging tile (128 bf16 + pad)
 
-  // Raw loads only, from a clamped index and without a use: nothing here waits for memory, so the
-  // operand loads of the k-loop are issued right behind these (n_valid >= 1 in every launch).
+  // The per-column scalars the epilogue needs (token id, exponent shift) are fetched before the k-loop
+  // straight into LDS (direct-to-LDS loads of 4 bytes per lane, from a clamped index; n_valid >= 1 in
+  // every launch) and read back after it: they wait for nothing, hold no registers across the loop, and
+  // are older than every operand load, so the loop's load counting is unchanged.  (Fetched into registers
+  // they either cost a wait before the first operand loads, or live across the loop, where the compiler
+  // spilled some of them and each reload in the epilogue waited for the stores in flight.)
   template <int NB> struct Pre { int y[NB]; float shift[NB]; };
+  template <int NB> static constexpr int stash_words() { return 2 * NB; }
   template <int NB>
-  __device__ __forceinline__ void prefetch(Pre<NB>& pre, int k0, int lane) const {
+  __device__ __forceinline__ void prefetch(int* words, int n_threads, int k0, int lane, int wave) const {
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) {
       const int kk = k0 + nb * 32 + (lane & 31);
       const int kc = kk < n_valid ? kk : n_valid - 1;
-      pre.y[nb] = ids[kc];
-      pre.shift[nb] = ref[kc];
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(ids + kc),
+                                       (__attribute__((address_space(3))) void*)(words + (2 * nb) * n_threads + wave * 64), 4, 0, 0);
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(ref + kc),
+                                       (__attribute__((address_space(3))) void*)(words + (2 * nb + 1) * n_threads + wave * 64), 4, 0, 0);
+    }
+  }
+  template <int NB>
+  __device__ __forceinline__ void unstash(Pre<NB>& pre, const int* words, int n_threads) const {
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) {
+      pre.y[nb] = words[(2 * nb) * n_threads + threadIdx.x];
+      pre.shift[nb] = __builtin_bit_cast(float, words[(2 * nb + 1) * n_threads + threadIdx.x]);
     }
   }
 
@@ -706,7 +731,9 @@ struct DHiddenEpilogue {
   int rows_p, cols_p;              // padded token rows / hidden columns of the launch
 
   template <int NB> struct Pre {};
-  template <int NB> __device__ __forceinline__ void prefetch(Pre<NB>&, int, int) const {}
+  template <int NB> static constexpr int stash_words() { return 0; }
+  template <int NB> __device__ __forceinline__ void prefetch(int*, int, int, int, int) const {}
+  template <int NB> __device__ __forceinline__ void unstash(Pre<NB>&, const int*, int) const {}
   template <int NB>
   __device__ __forceinline__ void operator()(f32x16 (&acc)[4][NB], const Pre<NB>&, int k0, int h0, int lane, int,
                                              char*, int slab_id) const {
@@ -746,7 +773,9 @@ struct DWeightEpilogue {
   float* partial;                  // tiles whose contraction is cut into ranges: [slab][256][256] fp32 raw sums
 
   template <int NB> struct Pre {};
-  template <int NB> __device__ __forceinline__ void prefetch(Pre<NB>&, int, int) const {}
+  template <int NB> static constexpr int stash_words() { return 0; }
+  template <int NB> __device__ __forceinline__ void prefetch(int*, int, int, int, int) const {}
+  template <int NB> __device__ __forceinline__ void unstash(Pre<NB>&, const int*, int) const {}
   // the wavefront's tile is MA x NB blocks of 32 x 32 (see the k-major branch of gemm_nt_kernel)
   template <int MA, int NB, class P>
   __device__ __forceinline__ void operator()(f32x16 (&acc)[MA][NB], const P&, int v0, int h0, int lane, int,

@@ -735,8 +735,8 @@ struct DHiddenEpilogue {
   template <int NB> __device__ __forceinline__ void prefetch(int*, int, int, int, int) const {}
   template <int NB> __device__ __forceinline__ void unstash(Pre<NB>&, const int*, int) const {}
   template <int NB>
-  __device__ __forceinline__ void operator()(f32x16 (&acc)[4][NB], const Pre<NB>&, int k0, int h0, int lane, int,
-                                             char*, int slab_id) const {
+  __device__ __forceinline__ void operator()(f32x16 (&acc)[4][NB], const Pre<NB>&, int k0, int h0, int lane, int wave,
+                                             char* lds, int slab_id) const {
     const int l32 = lane & 31, lhi = lane >> 5;
     if (slab_id >= 0) {            // this workgroup's range of the vocabulary: the raw sums go to its slab
       float* slab = partial + (int64_t)slab_id * rows_p * cols_p;
@@ -750,19 +750,32 @@ struct DHiddenEpilogue {
         }
       return;
     }
+    // 32 token rows at a time: beta_k * acc rounded to bf16 goes through this wavefront's own part of the LDS
+    // ring (free after the k-loop; rows of NB * 64 + 16 bytes) and leaves as 16-byte stores, whole rows of the
+    // wavefront's NB * 32 columns contiguous (2-byte stores straight from the accumulators took 80 k cycles
+    // per tile).  LDS operations of one wavefront execute in order: no barrier between its writes and reads.
+    constexpr int kRowBytes = NB * 64, kStageRow = kRowBytes + 16;
+    constexpr int kChunks = kRowBytes / 16, kRowsPerStore = 64 / kChunks;
+    char* stage = lds + wave * (32 * kStageRow);
 #pragma unroll
-    for (int mb = 0; mb < 4; ++mb)
+    for (int mb = 0; mb < 4; ++mb) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        const int k = k0 + mb * 32 + 8 * (r >> 2) + 4 * lhi + (r & 3);
-        if (k >= n_valid) continue;
-        const float b = beta[k];
+        const int row = 8 * (r >> 2) + 4 * lhi + (r & 3);
+        const int k = k0 + mb * 32 + row;
+        const float b = k < n_valid ? beta[k] : 0.f;
 #pragma unroll
-        for (int nb = 0; nb < NB; ++nb) {
-          const int h = h0 + nb * 32 + l32;
-          if (h < H) dH[(int64_t)k * H + h] = f32_to_bf16_bits(b * acc[mb][nb][r]);
-        }
+        for (int nb = 0; nb < NB; ++nb)
+          *(uint16_t*)(stage + row * kStageRow + (nb * 32 + l32) * 2) = f32_to_bf16_bits(b * acc[mb][nb][r]);
       }
+#pragma unroll
+      for (int i = 0; i < 32 / kRowsPerStore; ++i) {
+        const int row = i * kRowsPerStore + lane / kChunks, ch = lane % kChunks;
+        const uint4 val = *(const uint4*)(stage + row * kStageRow + ch * 16);
+        const int k = k0 + mb * 32 + row, h = h0 + ch * 8;
+        if (k < n_valid && h < H) *(uint4*)(dH + (int64_t)k * H + h) = val;     // H is a multiple of 8: whole chunks
+      }
+    }
   }
 };
 

@@ -50,9 +50,9 @@ constexpr int kStages = 4;                        // LDS ring of k-slices (4 x 3
 constexpr int kGranule = 128;                     // vocabulary rows per soft-max partial
 constexpr int kTileBytes = kBM * kBK * 2;         // 16 KiB per operand per stage
 // Wavefronts per workgroup of each contraction (4: one per SIMD, 128 x 128 each, 256 accumulator
-// registers; 8: two per SIMD, 128 x 64 each, so one can issue MFMAs while the other waits).
-// Measured on the Qwen3-8B head: the dW contraction is 3 % faster with 8, dH 2 % slower, the
-// logits contraction unchanged.
+// registers; 8: two per SIMD, 128 x 64 each: row-major operands only).  Measured on the Qwen3-8B
+// head with the row-major kernel: dH 2 % slower with 8, the logits contraction unchanged; the k-major
+// dW loop is written for 4.
 // Tile rows per group of the block -> tile map, per contraction (measured: 4 is 1-2 % faster than 8
 // for the two backward contractions, 2 and 6 are slower, 16 is 8 % slower).
 #ifndef NAT_GROUP_LOGITS
@@ -71,7 +71,7 @@ constexpr int kTileBytes = kBM * kBK * 2;         // 16 KiB per operand per stag
 #define NAT_WAVES_DHIDDEN 4
 #endif
 #ifndef NAT_WAVES_DWEIGHT
-#define NAT_WAVES_DWEIGHT 8
+#define NAT_WAVES_DWEIGHT 4
 #endif
 constexpr int kMaxChunk = 32768;                  // most token rows per chunk (see recommended_cap)
 constexpr int kNumCU = 256;                       // compute units (one workgroup of these kernels each)
@@ -192,20 +192,6 @@ __device__ __forceinline__ void tile_of_block(const GemmArgs& g, int pid, int& t
 // chunk index would fall on 4 bank groups, so the chunk is XOR-ed with bits 2..3 of the row.
 __device__ __forceinline__ int lds_chunk_off(int r, int c) { return r * (kBK * 2) + ((c ^ ((r >> 2) & 3)) << 4); }
 
-// Direct-to-LDS loads as inline assembly (two consecutive KiB: the second through the immediate
-// offset, which the hardware adds to both addresses).  Used by the kernel variant whose fragment
-// reads include the transposing LDS read: the compiler gives that read no memory operand and
-// therefore waits, before every such read, for ALL direct-to-LDS loads it knows to be outstanding
-// (vmcnt(0) inside the k-loop: measured 20-30 % slower).  Loads issued here are invisible to that
-// bookkeeping; the kernel orders them against the LDS reads itself (its own vmcnt waits and
-// barriers), exactly as the pipeline's design already requires.  m0 carries the LDS base; the
-// compiler keeps nothing in m0 across statements.
-__device__ __forceinline__ void dma_2kib(const uint16_t* gptr, const char* lds_dst) {
-  const uint32_t m0v = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(const __attribute__((address_space(3))) char*)lds_dst);
-  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off\n\tglobal_load_lds_dwordx4 %0, off offset:1024"
-               : : "v"(gptr), "s"(m0v) : "memory");
-}
-
 // Global -> LDS copy of one [256][32] bf16 operand block (16 KiB, contiguous in memory)
 // without staging registers: the NW wavefronts issue 16 direct-to-LDS loads of 16 bytes per
 // lane between them.  One instruction copies 1 KiB (16 tile rows) linearly: the hardware
@@ -223,10 +209,6 @@ struct TileLoader {
     src = base + (int64_t)tile * kb * kBlkElems + wave * (kLoads * 16 * kBK) + lane * 8;
   }
   __device__ __forceinline__ void start_at(int kt0) { src += (int64_t)kt0 * kBlkElems; }   // slice 0 := slice kt0
-  // the same through dma_2kib (see there): 2 KiB per call, half = 0 .. kLoads / 2 - 1
-  __device__ __forceinline__ void issue_asm(char* lds_tile, int kt, int wave, int half) const {
-    dma_2kib(src + (int64_t)kt * kBlkElems + half * 1024, lds_tile + wave * (kLoads * 1024) + half * 2048);
-  }
   // load kIdx = 0 .. kLoads - 1 of this wavefront's share
   template <int kIdx>
   __device__ __forceinline__ void issue_one(char* lds_tile, int kt, int wave) const {
@@ -259,8 +241,8 @@ struct TileLoader {
 // [row block][k][row within block], and fragments come out of it through the transposing LDS read.
 template <int NW>
 struct TileLoaderKMajor {
-  static constexpr int kLoads = kTileBytes / 1024 / NW;     // per wavefront: 4 or 2
-  static constexpr int kPieces = kLoads / 2;                // 2 KiB pieces per wavefront: 2 or 1
+  static constexpr int kLoads = kTileBytes / 1024 / NW;     // per wavefront (4 with 4 wavefronts)
+  static constexpr int kPieces = kLoads / 2;                // 2 KiB pieces per wavefront
   const uint16_t* src;           // this lane's 16 bytes of the wavefront's first piece, token tile 0, rows 0..15
   int64_t tile_stride;           // elements between consecutive token tiles of the source
 
@@ -269,14 +251,13 @@ struct TileLoaderKMajor {
     tile_stride = (int64_t)kb_src * kBlkElems;
   }
   __device__ __forceinline__ void start_at(int kt0) { src += (int64_t)(kt0 >> 3) * tile_stride; }   // kt0 % 8 == 0
-  __device__ __forceinline__ void issue(char* lds_tile, int kt, int wave) const {
-#pragma unroll
-    for (int piece = 0; piece < kPieces; ++piece) issue_asm(lds_tile, kt, wave, piece);
-  }
-  // piece = 0 .. kPieces - 1 of this wavefront, 2 KiB each, through dma_2kib (see there)
-  __device__ __forceinline__ void issue_asm(char* lds_tile, int kt, int wave, int piece) const {
-    dma_2kib(src + (int64_t)(kt >> 3) * tile_stride + (kt & 7) * 1024 + (int64_t)piece * kBlkElems,
-             lds_tile + (wave * kPieces + piece) * 2048);
+  // load kIdx = 0 .. kLoads - 1 of this wavefront's share (1 KiB: half a piece)
+  template <int kIdx>
+  __device__ __forceinline__ void issue_one(char* lds_tile, int kt, int wave) const {
+    constexpr int piece = kIdx >> 1;
+    __builtin_amdgcn_global_load_lds(
+        (const __attribute__((address_space(1))) void*)(src + (int64_t)(kt >> 3) * tile_stride + (kt & 7) * 1024 + (int64_t)piece * kBlkElems),
+        (__attribute__((address_space(3))) void*)(lds_tile + (wave * kPieces + piece) * 2048), 16, (kIdx & 1) * 1024, 0);
   }
 };
 
@@ -302,35 +283,6 @@ struct KMajorFragOffsets {
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef short s16x8 __attribute__((ext_vector_type(8)));
 
-// fragments of k-substep ks with A in the k-major tile: MA 32-row blocks from block a_blk0 (two
-// transposing reads each), NB blocks of B
-template <int MA, int NB>
-__device__ __forceinline__ void load_frags_kmajor(const char* a_s, const char* b_s, int a_blk0, int b_row0, int l32, int lhi,
-                                                  const KMajorFragOffsets& fo, int ks, bf16x8 (&af)[MA], bf16x8 (&bfr)[NB]) {
-#pragma unroll
-  for (int j = 0; j < NB; ++j) bfr[j] = *(const bf16x8*)(b_s + lds_chunk_off(b_row0 + j * 32 + l32, ks * 2 + lhi));
-#pragma unroll
-  for (int i = 0; i < MA; ++i) {
-    const char* piece = a_s + (a_blk0 + i) * 2048 + ks * 1024;
-    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(piece + fo.off[0]));
-    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(piece + fo.off[1]));
-    const s16x8 both = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
-    af[i] = __builtin_bit_cast(bf16x8, both);
-  }
-}
-
-// Scheduling hints for M MFMAs with R LDS reads spread over them as evenly as the counts allow.
-template <int M, int R, int I = 0>
-__device__ __forceinline__ void interleave_reads() {
-  if constexpr (I < M) {
-    constexpr int per = R / M, extra = R % M;
-    constexpr int n_i = per + (I < extra ? 1 : 0);
-    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-    if constexpr (n_i > 0) __builtin_amdgcn_sched_group_barrier(0x100, n_i, 0);
-    interleave_reads<M, R, I + 1>();
-  }
-}
-
 // One k-substep of the row-major loop, instruction slot by slot (the compiler may not move anything
 // across a slot's end): slot m holds MFMA m on the fragments (au, bu); behind each of the first 4 + NB
 // MFMAs one fragment read of k-substep ks_load from (a_s, b_s) into (al, bl); the remaining MFMAs carry
@@ -352,6 +304,42 @@ __device__ __forceinline__ void substep_slots(f32x16 (&acc)[4][NB], const bf16x8
       ld.template issue_one<(M - kLoadFirst) / kLoadEvery>(lds_dst, k, wave);
     __builtin_amdgcn_sched_barrier(0);
     substep_slots<NW, NB, M + 1>(acc, au, bu, al, bl, a_s, b_s, a_row0, b_row0, l32, lhi, ks_load, ld, lds_dst, k, wave);
+  }
+}
+
+__device__ __forceinline__ uint32_t lds_addr(const void* p) {
+  return (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) char*)p;
+}
+
+// The transposing read as inline assembly (byte offset as an immediate): invisible to the compiler's wait-count
+// pass, which would otherwise put a wait for all direct-to-LDS loads in front of it; the caller waits
+// (lgkmcnt) before it uses what was read.
+__device__ __forceinline__ s16x4 lds_read_tr16_b64(uint32_t addr, int off) {
+  s16x4 v;
+  asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "i"(off) : "memory");
+  return v;
+}
+
+// One k-substep of the k-major loop with 4 wavefronts of 128 x 128, slot by slot (see substep_slots): MFMA m on
+// (au, bu); behind the first 8 MFMAs one transposing read each (halves q = m % 2 of A block m / 2, from the
+// piece bases a_rd[q]) and behind the first 4 also one 16-byte read of B; behind MFMAs 8, 10, 12, 14 one
+// direct-to-LDS load of the refill (the A tile's when kRefillA, else the B tile's).
+template <bool kRefillA, int M = 0>
+__device__ __forceinline__ void substep_slots_kmajor4(f32x16 (&acc)[4][4], const bf16x8 (&au)[4], const bf16x8 (&bu)[4],
+                                                      s16x4 (&al)[8], bf16x8 (&bl)[4], const uint32_t (&a_rd)[2], const char* b_rd,
+                                                      const TileLoaderKMajor<4>& la, const TileLoader<4>& lb, char* lds_dst,
+                                                      int k, int wave) {
+  if constexpr (M < 16) {
+    constexpr int i = M / 4, j = M % 4;
+    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(au[i], bu[j], acc[i][j], 0, 0, 0);
+    if constexpr (M < 4) bl[M] = *(const bf16x8*)(b_rd + M * 2048);
+    if constexpr (M < 8) al[M] = lds_read_tr16_b64(a_rd[M & 1], (M / 2) * 2048);
+    if constexpr (M >= 8 && (M & 1) == 0) {
+      if constexpr (kRefillA) la.template issue_one<(M - 8) / 2>(lds_dst, k, wave);
+      else lb.template issue_one<(M - 8) / 2>(lds_dst, k, wave);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    substep_slots_kmajor4<kRefillA, M + 1>(acc, au, bu, al, bl, a_rd, b_rd, la, lb, lds_dst, k, wave);
   }
 }
 
@@ -448,82 +436,79 @@ gemm_nt_kernel(GemmArgs g, Epilogue epi) {
   }
 
   if constexpr (AT) {
-    // The pipeline described below (but with the whole refill under the last MFMAs of the second k-substep:
-    // splitting or spacing it measured 1-5 % slower here) with the k-major A operand: fragments through the transposing read
-    // (two per fragment), refill loads through dma_2kib, 2 KiB per statement.  The compiler schedules the
-    // fragment reads among the MFMAs as hinted; the refill statements are placed by hand behind the last
-    // MFMAs of the second substep, one per MFMA.
-    // The transposing read delivers half the bytes per clock of a 16-byte read (measured: ~110 against
-    // ~256 bytes per clock and CU), so with 8 wavefronts the wavefront tile is 64 rows of A by 128 columns
-    // of B: the A tile is then read by two wavefronts and the B tile by four, instead of four and two.
-    constexpr int MA = NW == 8 ? 2 : 4;                    // 32-row blocks of A per wavefront
-    constexpr int NT = 64 / (NW * MA);                     // 32-column blocks of B per wavefront (4)
-    constexpr int kWavesN = 8 / NT;                        // wavefronts along the columns
-    const int a_rowT = (wave / kWavesN) * (MA * 32), b_rowT = (wave % kWavesN) * (NT * 32);
-    constexpr int kMfmaT = MA * NT;                        // MFMAs per k-substep
-    constexpr int kDma = kLoadsPerWave / 2;                // refill statements per wavefront and slice (4 or 2)
-    constexpr int kReads = 2 * MA + NT;                    // LDS reads per k-substep
-    f32x16 accT[MA][NT];
-#pragma unroll
-    for (int i = 0; i < MA; ++i)
-#pragma unroll
-      for (int j = 0; j < NT; ++j)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) accT[i][j][r] = 0.f;
+    // k-major A: the row-major pipeline below (refill in two halves), with 4 wavefronts of 128 x 128, every
+    // instruction of the loop placed by hand (substep_slots_kmajor4), and the A fragments through the transposing
+    // read issued as inline assembly.  (The compiler's builtin for that read carries no memory operand, so its
+    // wait-count pass puts a wait for ALL direct-to-LDS loads in flight in front of every such read: vmcnt(0)
+    // inside the k-loop, 20-30 % slower.  As inline assembly the read is invisible to that pass; the kernel
+    // waits for it itself, lgkmcnt(0) before the next substep uses what was read.  An earlier variant kept the
+    // builtin read and hid the loads instead, with 8 wavefronts and compiler-scheduled reads: 3.5 % slower.)
+    static_assert(NW == 4, "the k-major loop is written for 4 wavefronts");
+    constexpr int kHalfLoads = kLoadsPerWave / 2;
     KMajorFragOffsets fo;
     fo.init(lane);
-    const int a_blk0 = a_rowT / 32;
-    auto refill = [&](int st, int k, int d) {              // statement d of the refill of stage st with slice k
-      if (d < kDma / 2) la.issue_asm(lds[st][0], k, wave, d);
-      else lb.issue_asm(lds[st][1], k, wave, d - kDma / 2);
-    };
+    const int a_blk0 = a_row0 / 32;
 #pragma unroll
-    for (int st = 0; st < kStages; ++st)
-#pragma unroll
-      for (int d = 0; d < kDma; ++d) refill(st, st < kt_n ? st : kt_n - 1, d);
-    __builtin_amdgcn_s_waitcnt(waitcnt_vm((kStages - 1) * kLoadsPerWave));
+    for (int st = 0; st < kStages; ++st) {
+      const int k = st < kt_n ? st : kt_n - 1;
+      la.template issue_one<0>(lds[st][0], k, wave);
+      la.template issue_one<1>(lds[st][0], k, wave);
+      la.template issue_one<2>(lds[st][0], k, wave);
+      la.template issue_one<3>(lds[st][0], k, wave);
+      if (st < kStages - 1) lb.issue(lds[st][1], k, wave);
+    }
+    __builtin_amdgcn_s_waitcnt(waitcnt_vm((2 * kStages - 3) * kHalfLoads));   // slice 0 has landed
     __syncthreads();
-    bf16x8 af[2][MA], bfr[2][NT];
-    load_frags_kmajor<MA, NT>(lds[0][0], lds[0][1], a_blk0, b_rowT, l32, lhi, fo, 0, af[0], bfr[0]);
-
+    s16x4 ah[2][8];
+    bf16x8 bfr[2][4];
+    auto a_bases = [&](int stage, int ks, uint32_t (&out)[2]) {
+      const uint32_t piece0 = lds_addr(lds[stage][0] + a_blk0 * 2048 + ks * 1024);
+      out[0] = piece0 + fo.off[0];
+      out[1] = piece0 + fo.off[1];
+    };
+    auto join = [&](const s16x4 (&h)[8], bf16x8 (&out)[4]) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const s16x8 both = {h[2 * i][0], h[2 * i][1], h[2 * i][2], h[2 * i][3], h[2 * i + 1][0], h[2 * i + 1][1], h[2 * i + 1][2], h[2 * i + 1][3]};
+        out[i] = __builtin_bit_cast(bf16x8, both);
+      }
+    };
+    {
+      uint32_t ar[2];
+      a_bases(0, 0, ar);
+#pragma unroll
+      for (int m = 0; m < 8; ++m) ah[0][m] = lds_read_tr16_b64(ar[m & 1], (m / 2) * 2048);
+#pragma unroll
+      for (int j = 0; j < 4; ++j) bfr[0][j] = *(const bf16x8*)(lds[0][1] + lds_chunk_off(b_row0 + j * 32 + l32, lhi));
+    }
     for (int kt = 0; kt < kt_n; ++kt) {
-      const int cur = kt % kStages, nxt = (kt + 1) % kStages;
-      // first k-substep of slice kt; the second substep's fragments are read under its MFMAs
-      load_frags_kmajor<MA, NT>(lds[cur][0], lds[cur][1], a_blk0, b_rowT, l32, lhi, fo, 1, af[1], bfr[1]);
-#pragma unroll
-      for (int m = 0; m < kMfmaT; ++m)
-        accT[m / NT][m % NT] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[0][m / NT], bfr[0][m % NT], accT[m / NT][m % NT], 0, 0, 0);
-      interleave_reads<kMfmaT, kReads>();
-#pragma unroll
-      for (int i = 0; i < MA; ++i)
-#pragma unroll
-        for (int j = 0; j < NT; ++j) asm volatile("" : "+a"(accT[i][j]));
+      const int cur = kt % kStages, nxt = (kt + 1) % kStages, last = (kt + kStages - 1) % kStages;
+      int k1 = kt + kStages - 1;
+      k1 = k1 < kt_n ? k1 : kt_n - 1;
+      int k2 = kt + kStages;
+      k2 = k2 < kt_n ? k2 : kt_n - 1;
+      uint32_t ar[2];
+      bf16x8 au[4];
+      // first k-substep of slice kt: reads its second substep's fragments, refills the B tile of slice kt + 3
+      a_bases(cur, 1, ar);
+      __builtin_amdgcn_s_waitcnt(0xc07f);                      // lgkmcnt(0): the fragments read under the last substep
+      join(ah[0], au);
       __builtin_amdgcn_sched_barrier(0);
-      // slice kt+1 has landed (this wavefront's share; the barrier covers the others) and this wavefront
-      // has finished reading slice kt, whose buffer is refilled below
+      substep_slots_kmajor4<false>(acc, au, bfr[0], ah[1], bfr[1], ar, lds[cur][1] + lds_chunk_off(b_row0 + l32, 2 + lhi),
+                                   la, lb, lds[last][1], k1, wave);
       __builtin_amdgcn_s_waitcnt(waitcnt_vm((kStages - 2) * kLoadsPerWave) & 0xf0ff);
       __builtin_amdgcn_s_barrier();
       __builtin_amdgcn_sched_barrier(0);
-      // second k-substep; under it the first fragments of slice kt+1, then the refill of lds[cur]
-      load_frags_kmajor<MA, NT>(lds[nxt][0], lds[nxt][1], a_blk0, b_rowT, l32, lhi, fo, 0, af[0], bfr[0]);
-      int k2 = kt + kStages;
-      k2 = k2 < kt_n ? k2 : kt_n - 1;
-      constexpr int kHead = kMfmaT - kDma;                 // MFMAs that carry the fragment reads
-#pragma unroll
-      for (int m = 0; m < kHead; ++m)
-        accT[m / NT][m % NT] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[1][m / NT], bfr[1][m % NT], accT[m / NT][m % NT], 0, 0, 0);
-      interleave_reads<kHead, kReads>();
+      // second k-substep: reads the first fragments of slice kt + 1, refills the A tile of lds[cur] with slice kt + 4
+      a_bases(nxt, 0, ar);
+      join(ah[1], au);
       __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-      for (int m = kHead; m < kMfmaT; ++m) {
-        accT[m / NT][m % NT] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[1][m / NT], bfr[1][m % NT], accT[m / NT][m % NT], 0, 0, 0);
-        refill(cur, k2, m - kHead);
-        __builtin_amdgcn_sched_barrier(0);
-      }
+      substep_slots_kmajor4<true>(acc, au, bfr[1], ah[0], bfr[0], ar, lds[nxt][1] + lds_chunk_off(b_row0 + l32, lhi),
+                                  la, lb, lds[cur][0], k2, wave);
     }
     __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));   // no direct-to-LDS load may outlive the block
     __syncthreads();
-    epi(accT, pre, m0 + a_rowT, n0 + b_rowT, lane, wave, &lds[0][0][0], slab);
+    epi(acc, pre, m0 + a_row0, n0 + b_row0, lane, wave, &lds[0][0][0], slab);
     return;
   } else {
   // Software pipeline over k-slices of 32.  Slice kt lives in lds[kt % 4]; three slices are
@@ -789,7 +774,7 @@ struct DWeightEpilogue {
   template <int NB> static constexpr int stash_words() { return 0; }
   template <int NB> __device__ __forceinline__ void prefetch(int*, int, int, int, int) const {}
   template <int NB> __device__ __forceinline__ void unstash(Pre<NB>&, const int*, int) const {}
-  // the wavefront's tile is MA x NB blocks of 32 x 32 (see the k-major branch of gemm_nt_kernel)
+  // the wavefront's tile is MA x NB blocks of 32 x 32
   template <int MA, int NB, class P>
   __device__ __forceinline__ void operator()(f32x16 (&acc)[MA][NB], const P&, int v0, int h0, int lane, int,
                                              char*, int slab_id) const {

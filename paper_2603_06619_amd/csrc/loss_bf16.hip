@@ -790,23 +790,37 @@ struct DWeightEpilogue {
             slab[((v0 & (kBM - 1)) + mb * 32 + 8 * (r >> 2) + 4 * lhi + (r & 3)) * kBN + (h0 & (kBN - 1)) + nb * 32 + l32] = acc[mb][nb][r];
       return;
     }
+    // One owner per element and launch, launches in stream order: the atomic sum is that of a
+    // read-modify-write, but the addition happens at the L2 and the workgroup does not wait for it.
+    // Addresses are a wave-uniform row pointer plus one per-lane offset (rows 4 * lhi further down, column
+    // l32), and the two launch-wide conditions (accumulate or overwrite, every row inside the vocabulary or
+    // the last tile's row check) are taken once, outside the loops: per element that leaves the store or
+    // atomic and a scalar add (per-element branches and 64-bit vector address arithmetic made this epilogue
+    // 31 k cycles per tile).
+    const uint32_t lane_off = (uint32_t)(4 * lhi) * (uint32_t)H + (uint32_t)l32;   // elements
+    const bool rows_ok = v0 + MA * 32 <= V;
+    auto sweep = [&](auto acc_mode, auto checked) {
 #pragma unroll
-    for (int nb = 0; nb < NB; ++nb) {
-      const int h = h0 + nb * 32 + l32;
-      if (h >= H) continue;
+      for (int nb = 0; nb < NB; ++nb) {
+        if (h0 + nb * 32 >= H) continue;                     // H is a multiple of 64: a 32-column block is in or out
 #pragma unroll
-      for (int mb = 0; mb < MA; ++mb)
+        for (int mb = 0; mb < MA; ++mb)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int v = v0 + mb * 32 + 8 * (r >> 2) + 4 * lhi + (r & 3);
-          if (v < V) {
-            float* p = dW + (int64_t)v * H + h;
-            // one owner per element and launch, launches in stream order: the sum is the same as a
-            // read-modify-write, but the addition happens at the L2 and the workgroup does not wait for it
-            if (accumulate) unsafeAtomicAdd(p, acc[mb][nb][r]);
+          for (int r = 0; r < 16; ++r) {
+            const int v = v0 + mb * 32 + 8 * (r >> 2) + (r & 3);   // row of lanes 0..31 (wave-uniform)
+            if (decltype(checked)::value && v + 4 * lhi >= V) continue;
+            float* p = dW + (int64_t)v * H + (h0 + nb * 32) + lane_off;
+            if (decltype(acc_mode)::value) unsafeAtomicAdd(p, acc[mb][nb][r]);
             else *p = acc[mb][nb][r];
           }
-        }
+      }
+    };
+    if (accumulate) {
+      if (rows_ok) sweep(std::true_type{}, std::false_type{});
+      else sweep(std::true_type{}, std::true_type{});
+    } else {
+      if (rows_ok) sweep(std::false_type{}, std::false_type{});
+      else sweep(std::false_type{}, std::true_type{});
     }
   }
 };

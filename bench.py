@@ -25,7 +25,7 @@ GEMM_CLASSES = ("logits_gemm", "dhidden_gemm", "dweight_gemm")
 # what the same counter reads for the library's row-gather copy kernel of known size
 # (factors 2.000 and 1.000; see profiles/).  Valid only for the kernel source they were taken
 # on: bench.py reports null when the source hash differs.
-TRAFFIC_SOURCE_SHA256_16 = "b899d45a3b63041a"
+TRAFFIC_SOURCE_SHA256_16 = "461c8f15aced70c5"
 TRAFFIC_BYTES_PER_LAUNCH = {
     "logits_gemm": 16826311490 + 2456013870,
     "dhidden_gemm": 14593432430 + 69123641,

@@ -353,15 +353,6 @@ __device__ __forceinline__ void load_frags(const char* a_s, const char* b_s, int
   for (int j = 0; j < NB; ++j) bfr[j] = *(const bf16x8*)(b_s + lds_chunk_off(b_row0 + j * 32 + l32, ks * 2 + lhi));
 }
 
-template <int NB>
-__device__ __forceinline__ void mfma_substep(f32x16 (&acc)[4][NB], const bf16x8 (&af)[4], const bf16x8 (&bfr)[NB]) {
-#pragma unroll
-  for (int i = 0; i < 4; ++i)
-#pragma unroll
-    for (int j = 0; j < NB; ++j)
-      acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
-}
-
 // s_waitcnt immediates (gfx9 encoding: vmcnt in bits 3:0 and 15:14, expcnt 6:4, lgkmcnt 11:8)
 constexpr int waitcnt_vm(int n) { return (n & 15) | ((n >> 4) << 14) | 0x0f70; }
 
@@ -375,7 +366,6 @@ __global__ void __launch_bounds__(NW * 64, 1)
 gemm_nt_kernel(GemmArgs g, Epilogue epi) {
   constexpr int NB = 16 / NW;                                  // 32-column blocks per wavefront
   constexpr int kLoadsPerWave = 2 * (kTileBytes / 1024) / NW;  // direct-to-LDS loads per wavefront per slice
-  constexpr int kMfma = 4 * NB, kFragReads = 4 + NB;           // per k-substep
   // one LDS object (with a second one the compiler's wait-count pass orders every fragment read behind all
   // direct-to-LDS loads in flight): the ring, and behind it the words the epilogue parks across the k-loop
   constexpr int kStashWords = Epilogue::template stash_words<16 / NW>();
@@ -1101,10 +1091,10 @@ size_t logp_bf16_workspace_bytes(int32_t N_k, int32_t H, int32_t V, bool minimal
   return make_fwd_plan(H, V, minimal ? kBN : recommended_cap(N_k, H, false)).total;
 }
 
-template <int NW, class Epi, bool AT = false>
+template <int NW, class Epi>
 static nat_status launch_gemm(const GemmArgs& g, const Epi& epi, int prof_class, hipStream_t s) {
   ProfScope prof(prof_class, s);
-  gemm_nt_kernel<Epi, NW, AT><<<g.tiles_m * g.tiles_n, NW * 64, 0, s>>>(g, epi);
+  gemm_nt_kernel<Epi, NW, false><<<g.tiles_m * g.tiles_n, NW * 64, 0, s>>>(g, epi);
   NAT_LAUNCH_CHECK();
   return NAT_OK;
 }
@@ -1243,7 +1233,6 @@ nat_status loss_bf16_run(const LossArgs& a) {
   NAT_LAUNCH_CHECK();
   return NAT_OK;
 }
-
 
 nat_status logp_bf16_run(const LogpArgs& a) {
   int cap = recommended_cap(a.N_k, a.H, false);

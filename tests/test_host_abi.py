@@ -45,6 +45,17 @@ def test_size_queries(lib):
     big = lib.nat_loss_workspace_bytes(100000, 4096, 151936, 1)
     small = lib.nat_loss_workspace_min_bytes(100000, 4096, 151936, 1)
     assert 0 < small < big < 32 * 2 ** 30
+    # the recommended workspace is bounded in N_k: chunks of 16384 tokens at H = 4096 (E = 16384 x Vp x 2 bytes
+    # of about 8 GB), of 32768 tokens where 16384 would leave the dH launch with a partly filled last round
+    GB = 1e9
+    at_8b = lib.nat_loss_workspace_bytes(145000, 4096, 151936, 1)
+    assert 7.9 * GB < at_8b < 8.1 * GB
+    assert lib.nat_loss_workspace_bytes(16384, 4096, 151936, 1) <= at_8b
+    assert lib.nat_loss_workspace_bytes(300000, 4096, 151936, 1) - at_8b < 1e6     # only the per-token terms grow
+    assert lib.nat_loss_workspace_bytes(8000, 4096, 151936, 1) < 0.7 * at_8b        # fewer tokens than a chunk
+    assert 12.9 * GB < lib.nat_loss_workspace_bytes(145000, 3584, 152064, 1) < 13.1 * GB
+    assert lib.nat_logp_workspace_bytes(300000, 4096, 151936, 1) == lib.nat_logp_workspace_bytes(145000, 4096, 151936, 1)
+    assert lib.nat_logp_workspace_bytes(145000, 4096, 151936, 1) < 2.0 * GB
     assert lib.nat_loss_workspace_bytes(10, 100, 512, 1) == 0          # bf16 needs H % 64 == 0
     assert lib.nat_loss_workspace_bytes(10, 64, 512, 0) > 0
     assert lib.nat_loss_workspace_bytes(10, 64, 512, 9) == 0
